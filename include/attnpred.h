@@ -1,0 +1,141 @@
+/*
+ * attnpred.h - C ABI of the AttentionPredictor decode hot path for AMD MI355X (gfx950).
+ *
+ * The calls follow the paper's problem statement (Sec. 3.2 "Problem Formulation") and Algorithm 1
+ * "Identify Critical Tokens": a history of block-max-pooled attention rows per KV head is run
+ * through the small CNN predictor, the top-K blocks are selected, decode attention runs over the
+ * selected blocks only and yields the next pooled row, which is pushed into the history.
+ *
+ * Vocabulary
+ *   instance  one (layer, batch, KV head) triple; instances never interact.       n_inst
+ *   g         query heads sharing the KV head (GQA group)
+ *   d         head_dim
+ *   b         block size (tokens pooled into one history column)
+ *   H         history length in rows (decode steps)
+ *   nb        ceil(t / b), blocks currently in the context;  nb_cap = t_cap / b
+ *   k         budget in blocks (B / b), including n_sink leading and n_local trailing forced blocks
+ *   R         ring slots of the history buffer, R = H + 1 (one spare row, see ap_hist_slots)
+ *
+ * Conventions
+ *   - Every pointer named below as "device" is a device pointer owned by the caller, contiguous
+ *     in the stated row-major shape and 16-byte aligned.  The library never frees or keeps them.
+ *   - `stream` is a hipStream_t passed as void*; all work is enqueued on it, nothing synchronises.
+ *   - Calls return AP_OK or a negative error code; an error found on the host leaves all outputs
+ *     untouched.  No call throws.  Only ap_create / ap_set_weights / ap_destroy allocate or free.
+ *   - All instances share one length t_cur per call.
+ *   - Inputs must be finite; NaN scores give an unspecified (but in-range, duplicate-free) selection.
+ */
+#ifndef ATTNPRED_H
+#define ATTNPRED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AP_OK 0
+#define AP_ERR_ARG (-1)         /* null pointer, non-positive size, inconsistent config            */
+#define AP_ERR_ALIGN (-2)       /* a device pointer is not 16-byte aligned                          */
+#define AP_ERR_RANGE (-3)       /* t_cur / nb_cur / slot outside what the context was created for  */
+#define AP_ERR_HIP (-4)         /* a HIP runtime call failed (allocation, copy, launch)             */
+#define AP_ERR_UNSUPPORTED (-5) /* shape outside the compiled kernel set                            */
+#define AP_ERR_STATE (-6)       /* predictor weights not set                                        */
+
+#define AP_F32 0
+#define AP_BF16 1
+
+typedef struct ap_ctx ap_ctx; /* opaque host object; owns only the device copy of the weights */
+
+typedef struct ap_config {
+  int32_t n_inst;   /* instances handled per call                                                   */
+  int32_t g;        /* query heads per KV head: 1, 2, 4 or 8                                        */
+  int32_t head_dim; /* 64 or 128                                                                    */
+  int32_t block;    /* b: power of two, 8..64                                                       */
+  int32_t hist_len; /* H: 1..256                                                                    */
+  int32_t t_cap;    /* token capacity of K/V, a multiple of b                                       */
+  int32_t k_blocks; /* k = B / b, n_sink + n_local <= k, k * b <= 4096                              */
+  int32_t n_sink;   /* forced leading blocks  (Sec. 4.1: prefix tokens are part of the budget)      */
+  int32_t n_local;  /* forced trailing blocks (Sec. 4.1: local tokens are part of the budget)       */
+  int32_t c1, c2;   /* predictor channels; compiled pairs: (4,4) (8,8) (16,32)                      */
+  int32_t kv_dtype; /* AP_F32 or AP_BF16: dtype of q, K and V                                       */
+} ap_config;
+
+/* Validates the configuration and creates a context (host object only, no device work).
+ * *out is untouched on error. */
+int ap_create(const ap_config* cfg, ap_ctx** out);
+int ap_destroy(ap_ctx* ctx);
+
+/* Bytes of caller-allocated device scratch that every per-step call takes as `ws` (16-B aligned).
+ * Its contents carry nothing between calls. */
+size_t ap_workspace_bytes(const ap_ctx* ctx);
+
+/* R, the number of row slots in the history ring (H + 1).  The history buffer is
+ * float hist[n_inst][R][nb_cap]; it must be zero-filled before the first push (missing early rows
+ * are zero rows, appendix "Training Details").  Row number n (0-based count of pushes) lives in
+ * slot n % R; the spare slot keeps the row that has just left the H-row window. */
+int32_t ap_hist_slots(const ap_ctx* ctx);
+int32_t ap_nb_cap(const ap_ctx* ctx);
+
+/* Predictor weights (architecture table, appendix "Implement Details"): host pointer to a flat fp32
+ * blob in the order w1[c1][3][3], b1[c1], w2[c2][c1][3][3], b2[c2], w3[c2], b3 - the layout of the
+ * corresponding Conv2d / Conv1d parameters, kernel axis 0 = time, axis 1 = block.  The blob is
+ * copied into device memory the context owns (allocated on the first call); the call waits for the
+ * copy on `stream`, so the caller may free the blob on return. */
+int ap_set_weights(ap_ctx* ctx, const float* host_blob, size_t n_floats, void* stream);
+
+/* Algorithm 1 step 4: pred = F(A_H) on the H x nb_cur tile (zero outside it at every conv layer),
+ * time average over H, raw linear head.
+ *   hist      device float [n_inst][R][nb_cap]
+ *   n_pushed  rows pushed so far; the newest row is in slot (n_pushed - 1) % R
+ *   pred      device float [n_inst][nb_cap]; entries [0, nb_cur) are written */
+int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur, float* pred,
+               void* ws, void* stream);
+
+/* Algorithm 1 step 5 with the budget split of Sec. 4.1: blocks [0, n_sink) and
+ * [nb_cur - n_local, nb_cur) are always selected; the other k - n_sink - n_local go to the
+ * highest pred among the blocks in between, equal scores to the lower index (-0 == +0).
+ * If nb_cur <= k every block is selected.
+ *   idx  device int32 [n_inst][k]   ascending block indices; entries beyond cnt are left alone
+ *   cnt  device int32 [n_inst]      number of valid entries (min(k, nb_cur)) */
+int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx, int32_t* cnt,
+                   void* ws, void* stream);
+
+/* Block-sparse decode attention (Sec. 3.1 restricted to the tokens of the selected blocks;
+ * Algorithm 1 step 6 is implicit: whole blocks are read) plus Algorithm 1 steps 1-2 as a
+ * by-product.  The caller has appended the new token's K/V, t_cur counts it; tokens >= t_cur of
+ * the last block are masked.
+ *   q    device [n_inst][g][d]      kv dtype
+ *   K,V  device [n_inst][t_cap][d]  kv dtype
+ *   idx  ascending, in [0, ceil(t_cur/b)); out-of-range entries are clamped into it
+ *   out  device float [n_inst][g][d]
+ *   row  device float [n_inst][nb_cap]: max over the group's heads and over the block's tokens of
+ *        the sparse softmax probability for selected blocks, 0 for all others (up to nb_cap) */
+int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, int32_t t_cur,
+                     const int32_t* idx, const int32_t* cnt, float* out, float* row, void* ws,
+                     void* stream);
+
+/* Distribution error calibration (Sec. 3.3): the pooled row of the dense attention of q over all
+ * t_cur tokens.  Reads K only and produces no attention output.
+ *   row  device float [n_inst][nb_cap]; entries >= ceil(t_cur/b) are written as 0 */
+int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float* row, void* ws,
+                 void* stream);
+
+/* Algorithm 1 step 3: push `row` as row number n_pushed (slot n_pushed % R), dropping the oldest.
+ * All nb_cap columns of the slot are written. */
+int ap_update_history(ap_ctx* ctx, float* hist, int64_t n_pushed, const float* row, void* stream);
+
+/* One fused decode step: predict -> select -> sparse decode -> push, with the pooled row written
+ * straight into ring slot n_pushed % R.  Equivalent to the four calls above in that order.
+ * pred, idx and cnt are outputs as in the single calls. */
+int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* K,
+            const void* V, int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred,
+            void* ws, void* stream);
+
+const char* ap_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTNPRED_H */

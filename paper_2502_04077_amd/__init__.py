@@ -1,0 +1,2 @@
+"""AttentionPredictor decode hot path for AMD MI355X: HIP kernels behind a C ABI + this thin binding."""
+from .binding import AP_BF16, AP_F32, ApError, Context, EXPORTS, load_library  # noqa: F401

@@ -1,0 +1,59 @@
+// Internal declarations shared by the kernel files and the C-ABI layer.  Not installed.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "attnpred.h"
+
+namespace ap {
+
+constexpr int kWave = 64;
+constexpr int kAttnThreads = 256;             // 4 waves per attention workgroup
+constexpr int kAttnWaves = kAttnThreads / kWave;
+constexpr int kGroupTokens = 16;              // tokens one wave covers per load group (4 x dwordx4 loads)
+constexpr int kCalibChunkTokens = 1024;       // tokens per calibration workgroup
+
+// Device-side layout of the predictor weights (all fp32), re-packed by ap_set_weights so that the
+// weights one inner loop iteration needs are contiguous:
+//   w1r[kh][kw][c1]            at 0
+//   b1[c1]                     at 9*c1
+//   w2r[ci][kh][kw][c2]        at 10*c1
+//   b2[c2]                     at 10*c1 + 9*c1*c2
+//   w3[c2]                     at 10*c1 + 9*c1*c2 + c2
+//   b3                         at 10*c1 + 9*c1*c2 + 2*c2
+struct Shape {
+  int n_inst, g, d, b, H, R, t_cap, nb_cap, k, n_sink, n_local, c1, c2, kv_dtype;
+  int n_split;        // workgroups per instance in sparse decode
+  int calib_chunks;   // max workgroups per instance in calibrate
+};
+
+// Workspace carve-up (float offsets from ws).
+struct WsLayout {
+  size_t part_ml;     // [n_inst][n_split][g][2]        split max / sum
+  size_t part_acc;    // [n_inst][n_split][g][d]        split un-normalised output
+  size_t part_bmp;    // [n_inst][g][k]                 per selected block: max prob relative to split max
+  size_t cal_ml;      // [n_inst][calib_chunks][g][2]
+  size_t cal_bmp;     // [n_inst][g][nb_cap]
+  size_t row_tmp;     // [n_inst][nb_cap]               unused by the fused step
+  size_t total;       // floats
+};
+
+WsLayout ws_layout(const Shape& s);
+
+// Launchers.  Each returns hipSuccess or the launch error.
+hipError_t launch_predict(const Shape& s, const float* dweights, const float* hist, int newest_slot,
+                          int nb_cur, float* pred, hipStream_t st);
+hipError_t launch_select(const Shape& s, const float* pred, int nb_cur, int32_t* idx, int32_t* cnt,
+                         hipStream_t st);
+// row_stride: floats between consecutive instances' rows (nb_cap for a plain row buffer,
+// R * nb_cap when writing straight into a ring slot).
+hipError_t launch_sparse_decode(const Shape& s, const void* q, const void* K, const void* V, int t_cur,
+                                const int32_t* idx, const int32_t* cnt, float* out, float* row,
+                                size_t row_stride, float* ws, hipStream_t st);
+hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row,
+                            float* ws, hipStream_t st);
+hipError_t launch_push_row(const Shape& s, float* hist, int slot, const float* row, hipStream_t st);
+
+}  // namespace ap

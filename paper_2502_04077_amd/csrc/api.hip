@@ -1,0 +1,238 @@
+// C ABI of the library: argument validation, context, workspace layout, launch sequencing.
+#include <new>
+#include <vector>
+
+#include "ap_internal.h"
+
+struct ap_ctx {
+  ap::Shape s;
+  float* dweights;      // device copy of the re-packed predictor weights, owned
+  bool have_weights;
+};
+
+namespace ap {
+
+static size_t align4(size_t x) { return (x + 3) & ~(size_t)3; }
+
+WsLayout ws_layout(const Shape& s) {
+  WsLayout w;
+  size_t o = 0;
+  w.part_ml = o;  o = align4(o + (size_t)s.n_inst * s.n_split * s.g * 2);
+  w.part_acc = o; o = align4(o + (size_t)s.n_inst * s.n_split * s.g * s.d);
+  w.part_bmp = o; o = align4(o + (size_t)s.n_inst * s.g * s.k);
+  w.cal_ml = o;   o = align4(o + (size_t)s.n_inst * s.calib_chunks * s.g * 2);
+  w.cal_bmp = o;  o = align4(o + (size_t)s.n_inst * s.g * s.nb_cap);
+  w.row_tmp = o;  o = align4(o + (size_t)s.n_inst * s.nb_cap);
+  w.total = o;
+  return w;
+}
+
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Workgroups per instance for sparse decode: enough to give the chip work when there are few
+// instances, at least one 16-token group per wave, and a logits tile that fits in 32 KiB of LDS.
+static int choose_split(const Shape& s) {
+  const int groups = (s.k * s.b + kGroupTokens - 1) / kGroupTokens;
+  const int by_work = groups / kAttnWaves > 1 ? groups / kAttnWaves : 1;
+  int want = (1024 + s.n_inst - 1) / s.n_inst;
+  if (want > by_work) want = by_work;
+  const int by_lds = (int)(((size_t)s.g * s.k * s.b * sizeof(float) + 32767) / 32768);
+  if (want < by_lds) want = by_lds;
+  if (want > s.k) want = s.k;
+  if (want < 1) want = 1;
+  const int per = (s.k + want - 1) / want;
+  return (s.k + per - 1) / per;
+}
+
+}  // namespace ap
+
+using ap::Shape;
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define AP_REQUIRE_PTR(p)                 \
+  do {                                    \
+    if ((p) == nullptr) return AP_ERR_ARG; \
+    if (!aligned16(p)) return AP_ERR_ALIGN; \
+  } while (0)
+
+extern "C" {
+
+int ap_create(const ap_config* c, ap_ctx** out) {
+  if (c == nullptr || out == nullptr) return AP_ERR_ARG;
+  if (c->n_inst <= 0 || c->t_cap <= 0 || c->hist_len <= 0 || c->k_blocks <= 0) return AP_ERR_ARG;
+  if (c->n_sink < 0 || c->n_local < 0 || c->n_sink + c->n_local > c->k_blocks) return AP_ERR_ARG;
+  if (!ap::pow2(c->block) || c->block < 8 || c->block > 64) return AP_ERR_UNSUPPORTED;
+  if (c->t_cap % c->block != 0) return AP_ERR_ARG;
+  if (c->g != 1 && c->g != 2 && c->g != 4 && c->g != 8) return AP_ERR_UNSUPPORTED;
+  if (c->head_dim != 64 && c->head_dim != 128) return AP_ERR_UNSUPPORTED;
+  if (c->kv_dtype != AP_F32 && c->kv_dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
+  if (c->hist_len > 256) return AP_ERR_UNSUPPORTED;
+  if ((int64_t)c->k_blocks * c->block > 4096) return AP_ERR_UNSUPPORTED;
+  const bool chan_ok = (c->c1 == 4 && c->c2 == 4) || (c->c1 == 8 && c->c2 == 8) || (c->c1 == 16 && c->c2 == 32);
+  if (!chan_ok) return AP_ERR_UNSUPPORTED;
+  if (c->n_inst > 65535) return AP_ERR_UNSUPPORTED;     // instances ride on gridDim.y
+
+  ap_ctx* ctx = new (std::nothrow) ap_ctx;
+  if (ctx == nullptr) return AP_ERR_ARG;
+  Shape& s = ctx->s;
+  s.n_inst = c->n_inst; s.g = c->g; s.d = c->head_dim; s.b = c->block; s.H = c->hist_len;
+  s.R = c->hist_len + 1; s.t_cap = c->t_cap; s.nb_cap = c->t_cap / c->block; s.k = c->k_blocks;
+  s.n_sink = c->n_sink; s.n_local = c->n_local; s.c1 = c->c1; s.c2 = c->c2; s.kv_dtype = c->kv_dtype;
+  s.n_split = ap::choose_split(s);
+  const int chunk_blocks = ap::kCalibChunkTokens / s.b;
+  s.calib_chunks = (s.nb_cap + chunk_blocks - 1) / chunk_blocks;
+  if ((size_t)s.calib_chunks * s.g * sizeof(float) > 60000) { delete ctx; return AP_ERR_UNSUPPORTED; }
+  ctx->dweights = nullptr;
+  ctx->have_weights = false;
+  *out = ctx;
+  return AP_OK;
+}
+
+int ap_destroy(ap_ctx* ctx) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  int rc = AP_OK;
+  if (ctx->dweights != nullptr && hipFree(ctx->dweights) != hipSuccess) rc = AP_ERR_HIP;
+  delete ctx;
+  return rc;
+}
+
+size_t ap_workspace_bytes(const ap_ctx* ctx) {
+  if (ctx == nullptr) return 0;
+  return ap::ws_layout(ctx->s).total * sizeof(float);
+}
+
+int32_t ap_hist_slots(const ap_ctx* ctx) { return ctx ? ctx->s.R : 0; }
+int32_t ap_nb_cap(const ap_ctx* ctx) { return ctx ? ctx->s.nb_cap : 0; }
+
+int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream) {
+  if (ctx == nullptr || blob == nullptr) return AP_ERR_ARG;
+  const int c1 = ctx->s.c1, c2 = ctx->s.c2;
+  const size_t expect = 9 * (size_t)c1 + c1 + 9 * (size_t)c1 * c2 + c2 + c2 + 1;
+  if (n_floats != expect) return AP_ERR_ARG;
+  const float* w1 = blob;                 // [c1][3][3]
+  const float* b1 = w1 + 9 * c1;
+  const float* w2 = b1 + c1;              // [c2][c1][3][3]
+  const float* b2 = w2 + 9 * (size_t)c1 * c2;
+  const float* w3 = b2 + c2;
+  const float* b3 = w3 + c2;
+  std::vector<float> packed(expect);
+  float* p = packed.data();
+  for (int t = 0; t < 9; ++t)
+    for (int c = 0; c < c1; ++c) p[t * c1 + c] = w1[c * 9 + t];
+  p += 9 * c1;
+  for (int c = 0; c < c1; ++c) p[c] = b1[c];
+  p += c1;
+  for (int ci = 0; ci < c1; ++ci)
+    for (int t = 0; t < 9; ++t)
+      for (int co = 0; co < c2; ++co) p[(ci * 9 + t) * c2 + co] = w2[((size_t)co * c1 + ci) * 9 + t];
+  p += 9 * (size_t)c1 * c2;
+  for (int c = 0; c < c2; ++c) p[c] = b2[c];
+  p += c2;
+  for (int c = 0; c < c2; ++c) p[c] = w3[c];
+  p += c2;
+  p[0] = b3[0];
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->dweights == nullptr &&
+      hipMalloc(reinterpret_cast<void**>(&ctx->dweights), expect * sizeof(float)) != hipSuccess) {
+    ctx->dweights = nullptr;
+    return AP_ERR_HIP;
+  }
+  if (hipMemcpyAsync(ctx->dweights, packed.data(), expect * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess)
+    return AP_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;   // `packed` dies on return
+  ctx->have_weights = true;
+  return AP_OK;
+}
+
+static int newest_slot_of(const Shape& s, int64_t n_pushed) {
+  return n_pushed <= 0 ? s.R - 1 : (int)((n_pushed - 1) % s.R);
+}
+
+int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur, float* pred, void* ws,
+               void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (!ctx->have_weights) return AP_ERR_STATE;
+  if (n_pushed < 0 || nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_predict(s, ctx->dweights, hist, newest_slot_of(s, n_pushed), nb_cur, pred,
+                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx, int32_t* cnt, void* ws,
+                   void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_select(s, pred, nb_cur, idx, cnt, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, int32_t t_cur,
+                     const int32_t* idx, const int32_t* cnt, float* out, float* row, void* ws, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(V); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  AP_REQUIRE_PTR(out); AP_REQUIRE_PTR(row); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_sparse_decode(s, q, K, V, t_cur, idx, cnt, out, row, (size_t)s.nb_cap,
+                                          static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float* row, void* ws, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(row); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_calibrate(s, q, K, t_cur, row, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_update_history(ap_ctx* ctx, float* hist, int64_t n_pushed, const float* row, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(row);
+  const Shape& s = ctx->s;
+  if (n_pushed < 0) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_push_row(s, hist, (int)(n_pushed % s.R), row, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* K, const void* V,
+            int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred, void* ws, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(V); AP_REQUIRE_PTR(out);
+  AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt); AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (!ctx->have_weights) return AP_ERR_STATE;
+  if (n_pushed < 0 || t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
+  const int nb_cur = (t_cur + s.b - 1) / s.b;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ap::launch_predict(s, ctx->dweights, hist, newest_slot_of(s, n_pushed), nb_cur, pred, st) != hipSuccess)
+    return AP_ERR_HIP;
+  if (ap::launch_select(s, pred, nb_cur, idx, cnt, st) != hipSuccess) return AP_ERR_HIP;
+  const int slot = (int)(n_pushed % s.R);
+  float* slot_row = hist + (size_t)slot * s.nb_cap;
+  if (ap::launch_sparse_decode(s, q, K, V, t_cur, idx, cnt, out, slot_row, (size_t)s.R * s.nb_cap,
+                               static_cast<float*>(ws), st) != hipSuccess)
+    return AP_ERR_HIP;
+  return AP_OK;
+}
+
+const char* ap_strerror(int code) {
+  switch (code) {
+    case AP_OK: return "ok";
+    case AP_ERR_ARG: return "invalid argument (null pointer, bad size or inconsistent configuration)";
+    case AP_ERR_ALIGN: return "device pointer is not 16-byte aligned";
+    case AP_ERR_RANGE: return "t_cur, nb_cur or n_pushed outside the range the context was created for";
+    case AP_ERR_HIP: return "a HIP runtime call failed";
+    case AP_ERR_UNSUPPORTED: return "shape outside the compiled kernel set";
+    case AP_ERR_STATE: return "predictor weights have not been set";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,494 @@
+// Block-sparse GQA decode attention and dense calibration for gfx950.
+//
+// Both kernels share the same first two phases:
+//   1. logits  l[h][tok] = (q_h . K_tok) / sqrt(d) for the tokens of a list of blocks, fp32
+//      accumulate, written to LDS (tokens at or beyond t_cur get -inf);
+//   2. per head: M = max l, p = exp(l - M) in place, L = sum p; per (head, block) the max p.
+// The sparse kernel continues with  3. acc[h][:] = sum_tok p[h][tok] * V_tok  and either finishes
+// (one workgroup per instance) or leaves (M, L, acc, block maxima) for the combine kernel.
+// Softmax definition: Sec. 3.1; block max-pooling of the probabilities: Algorithm 1 steps 1-2
+// (softmax is monotone, so the pooled probability of a block is exp(max logit - M) / L).
+//
+// Memory access: a K or V row is d * sizeof(T) bytes (256 B for bf16, d = 128).  LPT = row bytes / 16
+// adjacent lanes read one row with one 16-byte load each, so every load instruction of a wave covers
+// 64 / LPT whole rows = 1 KiB of contiguous memory inside a block.
+#include "ap_internal.h"
+
+namespace ap {
+namespace {
+
+struct bf16_t { uint16_t bits; };
+
+template <typename T> struct KvT;
+template <> struct KvT<float> { static constexpr int E = 4; };
+template <> struct KvT<bf16_t> { static constexpr int E = 8; };
+
+__device__ inline void unpack16(const uint4& w, float (&f)[4], float) {
+  f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
+  f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+}
+__device__ inline void unpack16(const uint4& w, float (&f)[8], bf16_t) {
+  f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
+  f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
+  f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
+  f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
+}
+
+template <int CTRL> __device__ inline float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the LPT adjacent lanes that share one token; every lane of the group gets the total.
+template <int LPT> __device__ inline float lane_group_sum(float v) {
+  v += dpp_move<0xB1>(v);                       // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);                       // quad_perm [2,3,0,1]
+  if (LPT >= 8) v += dpp_move<0x141>(v);        // row_half_mirror: pairs the two quads of 8 lanes
+  if (LPT >= 16) v += dpp_move<0x140>(v);       // row_mirror: pairs the two halves of 16 lanes
+  if (LPT >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T, int D, int G> struct Geom {
+  static constexpr int E = KvT<T>::E;           // elements per 16-byte load
+  static constexpr int LPT = D / E;             // lanes per token row
+  static constexpr int TPI = kWave / LPT;       // token rows per load instruction
+  static constexpr int NL = kGroupTokens / TPI; // load instructions per 16-token group
+  static_assert(LPT >= 8 && LPT <= 32 && G <= LPT, "unsupported geometry");
+};
+
+// Phase 1.  `block_of(jb)` gives the block index of list position jb.  s_p is [G][ld].
+template <typename T, int D, int G, class BlockOf>
+__device__ inline void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
+                                 int t_cur, int ntok, BlockOf block_of, float* s_p, int ld) {
+  using Ge = Geom<T, D, G>;
+  constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int dpart = lane % LPT;
+  const int tslot = lane / LPT;
+
+  float qr[G][E];
+  const float scale = rsqrtf((float)D);
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    static_assert(E * sizeof(T) == 16, "one 16-byte load per lane");
+    uint4 w = *reinterpret_cast<const uint4*>(q_inst + (size_t)h * D + dpart * E);
+    float f[E];
+    unpack16(w, f, T{});
+#pragma unroll
+    for (int e = 0; e < E; ++e) qr[h][e] = f[e] * scale;
+  }
+
+  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+  for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+    uint4 kw[NL];
+    int gtok[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int tau = grp * kGroupTokens + i * TPI + tslot;
+      kw[i] = make_uint4(0, 0, 0, 0);
+      gtok[i] = -1;
+      if (tau < ntok) {
+        const int blk = block_of(tau >> log2b);
+        gtok[i] = blk * b + (tau & (b - 1));
+        kw[i] = *reinterpret_cast<const uint4*>(K_inst + (size_t)gtok[i] * D + dpart * E);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int tau = grp * kGroupTokens + i * TPI + tslot;
+      float kf[E];
+      unpack16(kw[i], kf, T{});
+      float mine = 0.f;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) s = fmaf(qr[h][e], kf[e], s);
+        s = lane_group_sum<LPT>(s);
+        if (dpart == h) mine = s;
+      }
+      if (dpart < G && tau < ntok) s_p[dpart * ld + tau] = (gtok[i] < t_cur) ? mine : -INFINITY;
+    }
+  }
+}
+
+// Phase 2.  Leaves p in s_p, (M, L) in s_m / s_l, per (head, block) max p in s_bmp[h * nblk + jb].
+template <int G>
+__device__ inline void softmax_stats(float* s_p, int ld, int ntok, int b, int nblk, float* s_m, float* s_l,
+                                     float* s_bmp) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  for (int h = wave; h < G; h += kAttnWaves) {
+    float m = -INFINITY;
+    for (int tau = lane; tau < ntok; tau += kWave) m = fmaxf(m, s_p[h * ld + tau]);
+    m = wave_max(m);
+    float sum = 0.f;
+    for (int tau = lane; tau < ntok; tau += kWave) {
+      const float p = __expf(s_p[h * ld + tau] - m);
+      s_p[h * ld + tau] = p;
+      sum += p;
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) { s_m[h] = m; s_l[h] = sum; }
+  }
+  __syncthreads();
+  for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+    const int h = pair / nblk, jb = pair - h * nblk;
+    const int t0 = jb * b;
+    const int t1 = min(t0 + b, ntok);
+    float mx = 0.f;
+    for (int tau = t0; tau < t1; ++tau) mx = fmaxf(mx, s_p[h * ld + tau]);
+    s_bmp[pair] = mx;
+  }
+  __syncthreads();
+}
+
+// Writes one instance's pooled row: rowval[pos] at column idx[pos] (idx ascending), 0 elsewhere.
+__device__ inline void write_row(float* __restrict__ row, int nb_cap, const int* s_idx, int cnt,
+                                 const float* s_rowval) {
+  for (int j = threadIdx.x; j < nb_cap; j += blockDim.x) {
+    int lo = 0, hi = cnt;                       // first position with idx >= j
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (s_idx[mid] < j) lo = mid + 1; else hi = mid;
+    }
+    row[j] = (lo < cnt && s_idx[lo] == j) ? s_rowval[lo] : 0.f;
+  }
+}
+
+struct SparseArgs {
+  const void* q; const void* K; const void* V;
+  const int32_t* idx; const int32_t* cnt;
+  float* out; float* row; size_t row_stride;
+  float* part_ml; float* part_acc; float* part_bmp;
+  int t_cap, nb_cap, k, b, log2b, t_cur, nb_cur, n_split, blk_per_split;
+};
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void sparse_decode_kernel(SparseArgs a) {
+  using Ge = Geom<T, D, G>;
+  constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
+  extern __shared__ __align__(16) float smem[];
+  const int inst = blockIdx.y, split = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int dpart = lane % LPT, tslot = lane / LPT;
+
+  const int cnt = min(max(a.cnt[inst], 0), a.k);
+  // With one workgroup per instance the whole list is local; otherwise this split's slice.
+  const int j0 = (a.n_split == 1) ? 0 : min(cnt, split * a.blk_per_split);
+  const int j1 = (a.n_split == 1) ? cnt : min(cnt, j0 + a.blk_per_split);
+  const int nblk = j1 - j0;
+  const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
+  const int ld = nblk_cap * a.b;
+  const int ntok = nblk * a.b;
+
+  float* s_p = smem;                                   // [G][ld]
+  float* s_acc = s_p + G * ld;                         // [waves][G][D]
+  float* s_bmp = s_acc + kAttnWaves * G * D;           // [G][nblk_cap]
+  float* s_rowval = s_bmp + G * nblk_cap;              // [nblk_cap]
+  float* s_m = s_rowval + nblk_cap;                    // [G]
+  float* s_l = s_m + G;                                // [G]
+  int* s_idx = reinterpret_cast<int*>(s_l + G);        // [nblk_cap]
+
+  for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
+    s_idx[j] = min(max(a.idx[(size_t)inst * a.k + j0 + j], 0), a.nb_cur - 1);
+  __syncthreads();
+
+  const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
+  const T* K_inst = static_cast<const T*>(a.K) + (size_t)inst * a.t_cap * D;
+  const T* V_inst = static_cast<const T*>(a.V) + (size_t)inst * a.t_cap * D;
+
+  float acc[G][E];
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
+
+  if (nblk > 0) {
+    qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; }, s_p, ld);
+    __syncthreads();
+    softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
+
+    // Phase 3: acc += p * V, same token-to-lane mapping as phase 1.
+    const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      uint4 vw[NL];
+      int tau_i[NL];
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int tau = grp * kGroupTokens + i * TPI + tslot;
+        tau_i[i] = tau < ntok ? tau : -1;
+        vw[i] = make_uint4(0, 0, 0, 0);
+        if (tau < ntok) {
+          const int gtok = s_idx[tau >> a.log2b] * a.b + (tau & (a.b - 1));
+          vw[i] = *reinterpret_cast<const uint4*>(V_inst + (size_t)gtok * D + dpart * E);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        float vf[E];
+        unpack16(vw[i], vf, T{});
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          const float p = tau_i[i] >= 0 ? s_p[h * ld + tau_i[i]] : 0.f;
+#pragma unroll
+          for (int e = 0; e < E; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
+        }
+      }
+    }
+  } else {
+    if (threadIdx.x < G) { s_m[threadIdx.x] = -INFINITY; s_l[threadIdx.x] = 0.f; }
+  }
+
+  // Sum the token slots of a wave (lanes that hold the same dims), then the waves through LDS.
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      float v = acc[h][e];
+#pragma unroll
+      for (int o = LPT; o < kWave; o <<= 1) v += __shfl_xor(v, o, 64);
+      acc[h][e] = v;
+    }
+  if (tslot == 0) {
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int e = 0; e < E; ++e) s_acc[(wave * G + h) * D + dpart * E + e] = acc[h][e];
+  }
+  __syncthreads();
+
+  if (a.n_split == 1) {
+    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
+      a.out[(size_t)inst * G * D + o] = v / s_l[o / D];
+    }
+    for (int jb = threadIdx.x; jb < nblk; jb += kAttnThreads) {
+      float mx = 0.f;
+#pragma unroll
+      for (int h = 0; h < G; ++h) mx = fmaxf(mx, s_bmp[h * nblk + jb] / s_l[h]);
+      s_rowval[jb] = mx;
+    }
+    __syncthreads();
+    write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, nblk, s_rowval);
+  } else {
+    const size_t ps = (size_t)inst * a.n_split + split;
+    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
+      a.part_acc[ps * G * D + o] = v;
+    }
+    if (threadIdx.x < G) {
+      a.part_ml[(ps * G + threadIdx.x) * 2 + 0] = s_m[threadIdx.x];
+      a.part_ml[(ps * G + threadIdx.x) * 2 + 1] = s_l[threadIdx.x];
+    }
+    for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+      const int h = pair / nblk, jb = pair - h * nblk;
+      a.part_bmp[((size_t)inst * G + h) * a.k + j0 + jb] = s_bmp[pair];
+    }
+  }
+}
+
+// Merges the splits of one instance: global (M, L) per head, normalised output, pooled row.
+template <int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs a) {
+  extern __shared__ __align__(16) float smem[];
+  const int inst = blockIdx.x;
+  const int cnt = min(max(a.cnt[inst], 0), a.k);
+  float* s_scale = smem;                               // [n_split][G]  exp(m_s - M) / L
+  float* s_rowval = s_scale + a.n_split * G;           // [k]
+  int* s_idx = reinterpret_cast<int*>(s_rowval + a.k); // [k]
+
+  for (int j = threadIdx.x; j < cnt; j += kAttnThreads)
+    s_idx[j] = min(max(a.idx[(size_t)inst * a.k + j], 0), a.nb_cur - 1);
+  if (threadIdx.x < G) {
+    const int h = threadIdx.x;
+    const float* ml = a.part_ml + ((size_t)inst * a.n_split * G + h) * 2;
+    float M = -INFINITY;
+    for (int s = 0; s < a.n_split; ++s) M = fmaxf(M, ml[(size_t)s * G * 2]);
+    float L = 0.f;
+    for (int s = 0; s < a.n_split; ++s) {
+      const float m = ml[(size_t)s * G * 2];
+      const float sc = (m == -INFINITY) ? 0.f : __expf(m - M);
+      s_scale[s * G + h] = sc;
+      L += ml[(size_t)s * G * 2 + 1] * sc;
+    }
+    const float invL = 1.f / L;
+    for (int s = 0; s < a.n_split; ++s) s_scale[s * G + h] *= invL;
+  }
+  __syncthreads();
+  for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+    const int h = o / D;
+    float v = 0.f;
+    for (int s = 0; s < a.n_split; ++s)
+      v = fmaf(a.part_acc[((size_t)inst * a.n_split + s) * G * D + o], s_scale[s * G + h], v);
+    a.out[(size_t)inst * G * D + o] = v;
+  }
+  for (int jb = threadIdx.x; jb < cnt; jb += kAttnThreads) {
+    const int s = jb / a.blk_per_split;
+    float mx = 0.f;
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+      mx = fmaxf(mx, a.part_bmp[((size_t)inst * G + h) * a.k + jb] * s_scale[s * G + h]);
+    s_rowval[jb] = mx;
+  }
+  __syncthreads();
+  write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, cnt, s_rowval);
+}
+
+struct CalibArgs {
+  const void* q; const void* K;
+  float* row; float* cal_ml; float* cal_bmp;
+  int t_cap, nb_cap, b, log2b, t_cur, nb_cur, chunk_blocks, n_chunks, chunk_slots;
+};
+
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kAttnThreads) void calibrate_kernel(CalibArgs a) {
+  extern __shared__ __align__(16) float smem[];
+  const int inst = blockIdx.y, chunk = blockIdx.x;
+  const int c0 = chunk * a.chunk_blocks;
+  const int nblk = min(a.chunk_blocks, a.nb_cur - c0);
+  const int ld = a.chunk_blocks * a.b;
+  const int ntok = nblk * a.b;
+  float* s_p = smem;                    // [G][ld]
+  float* s_bmp = s_p + G * ld;          // [G][chunk_blocks]
+  float* s_m = s_bmp + G * a.chunk_blocks;
+  float* s_l = s_m + G;
+
+  const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
+  const T* K_inst = static_cast<const T*>(a.K) + (size_t)inst * a.t_cap * D;
+  qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; }, s_p, ld);
+  __syncthreads();
+  softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
+  for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+    const int h = pair / nblk, jb = pair - h * nblk;
+    a.cal_bmp[((size_t)inst * G + h) * a.nb_cap + c0 + jb] = s_bmp[pair];
+  }
+  if (threadIdx.x < G) {
+    float* ml = a.cal_ml + (((size_t)inst * a.chunk_slots + chunk) * G + threadIdx.x) * 2;
+    ml[0] = s_m[threadIdx.x];
+    ml[1] = s_l[threadIdx.x];
+  }
+}
+
+template <int G>
+__global__ __launch_bounds__(kAttnThreads) void calibrate_finish_kernel(CalibArgs a) {
+  extern __shared__ __align__(16) float smem[];
+  const int inst = blockIdx.x;
+  float* s_scale = smem;                // [n_chunks][G]
+  if (threadIdx.x < G) {
+    const int h = threadIdx.x;
+    const float* ml = a.cal_ml + ((size_t)inst * a.chunk_slots * G + h) * 2;
+    float M = -INFINITY;
+    for (int c = 0; c < a.n_chunks; ++c) M = fmaxf(M, ml[(size_t)c * G * 2]);
+    float L = 0.f;
+    for (int c = 0; c < a.n_chunks; ++c) {
+      const float sc = __expf(ml[(size_t)c * G * 2] - M);
+      s_scale[c * G + h] = sc;
+      L += ml[(size_t)c * G * 2 + 1] * sc;
+    }
+    const float invL = 1.f / L;
+    for (int c = 0; c < a.n_chunks; ++c) s_scale[c * G + h] *= invL;
+  }
+  __syncthreads();
+  float* row = a.row + (size_t)inst * a.nb_cap;
+  for (int j = threadIdx.x; j < a.nb_cap; j += kAttnThreads) {
+    float mx = 0.f;
+    if (j < a.nb_cur) {
+      const int c = j / a.chunk_blocks;
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+        mx = fmaxf(mx, a.cal_bmp[((size_t)inst * G + h) * a.nb_cap + j] * s_scale[c * G + h]);
+    }
+    row[j] = mx;
+  }
+}
+
+int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
+
+template <typename T, int D, int G>
+hipError_t run_sparse(const Shape& s, SparseArgs a, hipStream_t st) {
+  const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
+  const size_t lds = sizeof(float) * ((size_t)G * nblk_cap * a.b + kAttnWaves * G * D + G * nblk_cap + nblk_cap + 2 * G) +
+                     sizeof(int) * nblk_cap;
+  sparse_decode_kernel<T, D, G><<<dim3(a.n_split, s.n_inst), kAttnThreads, lds, st>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.n_split == 1) return e;
+  const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G + a.k) + sizeof(int) * a.k;
+  sparse_combine_kernel<D, G><<<dim3(s.n_inst), kAttnThreads, lds2, st>>>(a);
+  return hipGetLastError();
+}
+
+template <typename T, int D, int G>
+hipError_t run_calib(const Shape& s, CalibArgs a, hipStream_t st) {
+  const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G);
+  calibrate_kernel<T, D, G><<<dim3(a.n_chunks, s.n_inst), kAttnThreads, lds, st>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  calibrate_finish_kernel<G><<<dim3(s.n_inst), kAttnThreads, sizeof(float) * a.n_chunks * G, st>>>(a);
+  return hipGetLastError();
+}
+
+#define AP_DISPATCH_G(FN, T, D, ...)                              \
+  switch (s.g) {                                                  \
+    case 1: return FN<T, D, 1>(__VA_ARGS__);                      \
+    case 2: return FN<T, D, 2>(__VA_ARGS__);                      \
+    case 4: return FN<T, D, 4>(__VA_ARGS__);                      \
+    case 8: return FN<T, D, 8>(__VA_ARGS__);                      \
+    default: return hipErrorInvalidValue;                         \
+  }
+#define AP_DISPATCH(FN, ...)                                                      \
+  if (s.kv_dtype == AP_BF16) {                                                    \
+    if (s.d == 128) { AP_DISPATCH_G(FN, bf16_t, 128, __VA_ARGS__) }               \
+    if (s.d == 64) { AP_DISPATCH_G(FN, bf16_t, 64, __VA_ARGS__) }                 \
+  } else {                                                                        \
+    if (s.d == 128) { AP_DISPATCH_G(FN, float, 128, __VA_ARGS__) }                \
+    if (s.d == 64) { AP_DISPATCH_G(FN, float, 64, __VA_ARGS__) }                  \
+  }                                                                               \
+  return hipErrorInvalidValue;
+
+}  // namespace
+
+hipError_t launch_sparse_decode(const Shape& s, const void* q, const void* K, const void* V, int t_cur,
+                                const int32_t* idx, const int32_t* cnt, float* out, float* row,
+                                size_t row_stride, float* ws, hipStream_t st) {
+  const WsLayout wl = ws_layout(s);
+  SparseArgs a;
+  a.q = q; a.K = K; a.V = V; a.idx = idx; a.cnt = cnt; a.out = out; a.row = row; a.row_stride = row_stride;
+  a.part_ml = ws + wl.part_ml; a.part_acc = ws + wl.part_acc; a.part_bmp = ws + wl.part_bmp;
+  a.t_cap = s.t_cap; a.nb_cap = s.nb_cap; a.k = s.k; a.b = s.b; a.log2b = ilog2(s.b); a.t_cur = t_cur;
+  a.nb_cur = (t_cur + s.b - 1) / s.b;
+  a.n_split = s.n_split;
+  a.blk_per_split = (s.k + s.n_split - 1) / s.n_split;
+  AP_DISPATCH(run_sparse, s, a, st)
+}
+
+hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row, float* ws,
+                            hipStream_t st) {
+  const WsLayout wl = ws_layout(s);
+  CalibArgs a;
+  a.q = q; a.K = K; a.row = row; a.cal_ml = ws + wl.cal_ml; a.cal_bmp = ws + wl.cal_bmp;
+  a.t_cap = s.t_cap; a.nb_cap = s.nb_cap; a.b = s.b; a.log2b = ilog2(s.b); a.t_cur = t_cur;
+  a.nb_cur = (t_cur + s.b - 1) / s.b;
+  a.chunk_blocks = kCalibChunkTokens / s.b;
+  a.n_chunks = (a.nb_cur + a.chunk_blocks - 1) / a.chunk_blocks;
+  a.chunk_slots = s.calib_chunks;
+  AP_DISPATCH(run_calib, s, a, st)
+}
+
+}  // namespace ap

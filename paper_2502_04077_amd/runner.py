@@ -1,0 +1,69 @@
+"""Device buffers and call sequencing for a Workload: allocation and bookkeeping only.
+
+Holds the tensors one decode run needs (history ring, pred, idx, out, row, workspace) and drives
+the C-ABI calls in the order of Algorithm 1.  No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import torch
+
+from .binding import Context
+
+
+class DecodeRun:
+    def __init__(self, w, device="cuda:0"):
+        self.w = w
+        self.dev = torch.device(device)
+        self.ctx = Context(n_inst=w.n_inst, g=w.g, head_dim=w.head_dim, block=w.block, hist_len=w.hist_len,
+                           t_cap=w.t_cap, k_blocks=w.k_blocks, n_sink=w.n_sink, n_local=w.n_local,
+                           c1=w.c1, c2=w.c2, kv_dtype=w.kv_dtype)
+        R, nbc = self.ctx.hist_slots(), self.ctx.nb_cap()
+        self.R, self.nb_cap = R, nbc
+        f32, i32 = torch.float32, torch.int32
+        self.hist = torch.zeros((w.n_inst, R, nbc), dtype=f32, device=self.dev)
+        self.pred = torch.zeros((w.n_inst, nbc), dtype=f32, device=self.dev)
+        self.row = torch.zeros((w.n_inst, nbc), dtype=f32, device=self.dev)
+        self.idx = torch.zeros((w.n_inst, w.k_blocks), dtype=i32, device=self.dev)
+        self.cnt = torch.zeros((w.n_inst,), dtype=i32, device=self.dev)
+        self.out = torch.zeros((w.n_inst, w.g, w.head_dim), dtype=f32, device=self.dev)
+        self.ws = torch.zeros((max(16, self.ctx.workspace_bytes()),), dtype=torch.uint8, device=self.dev)
+        self.n_pushed = 0
+
+    def set_weights(self, blob):
+        self.ctx.set_weights(blob)
+
+    def nb(self, t):
+        return (t + self.w.block - 1) // self.w.block
+
+    def logical_history(self) -> torch.Tensor:
+        """The H-row window in logical order (index H-1 = newest) as a new tensor [n_inst][H][nb_cap]."""
+        H, R = self.w.hist_len, self.R
+        slots = [(self.n_pushed - H + r) % R for r in range(H)]
+        h = self.hist[:, slots, :].clone()
+        for r in range(H):
+            if self.n_pushed - H + r < 0:
+                h[:, r, :] = 0
+        return h
+
+    def warmup_calibrate(self, q, K, t):
+        """Push the dense pooled row of (q, K[:t]) - used for the prefill tail and calibration."""
+        self.ctx.calibrate(q, K, t, self.row, self.ws)
+        self.ctx.update_history(self.hist, self.n_pushed, self.row)
+        self.n_pushed += 1
+
+    def step_unfused(self, q, K, V, t, calibrate=False):
+        nb = self.nb(t)
+        self.ctx.predict(self.hist, self.n_pushed, nb, self.pred, self.ws)
+        self.ctx.select_topk(self.pred, nb, self.idx, self.cnt, self.ws)
+        self.ctx.sparse_decode(q, K, V, t, self.idx, self.cnt, self.out, self.row, self.ws)
+        if calibrate:
+            self.ctx.calibrate(q, K, t, self.row, self.ws)
+        self.ctx.update_history(self.hist, self.n_pushed, self.row)
+        self.n_pushed += 1
+
+    def step(self, q, K, V, t, calibrate=False):
+        self.ctx.step(self.hist, self.n_pushed, q, K, V, t, self.out, self.idx, self.cnt, self.pred, self.ws)
+        if calibrate:
+            self.ctx.calibrate(q, K, t, self.row, self.ws)
+            self.ctx.update_history(self.hist, self.n_pushed, self.row)
+        self.n_pushed += 1
