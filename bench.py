@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Decode-step throughput of the AttentionPredictor hot path on one MI355X.
+
+One step = predict + top-k select + block-sparse decode attention + history push for every
+instance of the workload (fused `ap_step`), plus the dense calibration call on every M-th step.
+Inputs are synthetic, seeded and resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 4 SIMD x 16 lanes x 2 (FMA) x 2 (packed) x 2.4 GHz, published
+
+
+def algorithmic_bytes(w, t):
+    """HBM bytes Algorithm 1 itself has to move per instance for one call of each kernel."""
+    s_kv = 2 if w.kv_dtype == "bf16" else 4
+    nb = (t + w.block - 1) // w.block
+    k = min(w.k_blocks, nb)
+    return {
+        "predict": w.hist_len * nb * 4 + nb * 4,
+        "select": nb * 4 + k * 4,
+        "sparse_decode": 2 * k * w.block * w.head_dim * s_kv + w.g * w.head_dim * (s_kv + 4) + k * 4 + nb * 4,
+        "calibrate": t * w.head_dim * s_kv + w.g * w.head_dim * s_kv + nb * 4,
+    }
+
+
+def algorithmic_flops(w, t):
+    nb = (t + w.block - 1) // w.block
+    k = min(w.k_blocks, nb)
+    return {
+        "predict": 2 * (9 * w.c1 + 9 * w.c1 * w.c2) * w.hist_len * nb + 2 * w.c2 * nb,
+        "sparse_decode": 4 * w.g * w.head_dim * k * w.block,
+    }
+
+
+def cpu_baseline(w, run, K, V, budget_s=20.0, max_inst=16):
+    """Times the oracle's decode_step as it stands on a bounded sample of instances."""
+    import numpy as np
+    import torch
+    from oracle import attnpred_oracle as orc
+    from workloads import predictor_weights, queries, to_f64
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    wts = orc.PredictorWeights.from_blob(predictor_weights(w), w.c1, w.c2)
+    hist = run.logical_history()
+    t = w.t_at(0)
+    q = queries(w, 0, run.dev)
+    n_done, t_used = 0, 0.0
+    for i in range(min(max_inst, w.n_inst)):
+        h = hist[i].cpu().numpy().astype(np.float64)
+        qi, Ki, Vi = to_f64(q[i]), to_f64(K[i]), to_f64(V[i])
+        t0 = time.perf_counter()
+        orc.decode_step(h, qi, Ki, Vi, t, wts, b=w.block, k=w.k_blocks, n_sink=w.n_sink, n_local=w.n_local,
+                        calibrate=False)
+        t_used += time.perf_counter() - t0
+        n_done += 1
+        if t_used > budget_s:
+            break
+    per_inst = t_used / n_done
+    return {
+        "value": 1.0 / (per_inst * w.n_inst), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{n_done} of {w.n_inst} instances x 1 non-calibration decode step of {w.name}, "
+                  f"{per_inst * 1e3:.1f} ms per instance-step, extrapolated to all instances",
+    }
+
+
+def main():
+    ap_ = argparse.ArgumentParser()
+    ap_.add_argument("--gpus", type=int, default=1)
+    ap_.add_argument("--steps", type=int, default=64)
+    ap_.add_argument("--warmup", type=int, default=4)
+    ap_.add_argument("--workload", default="cfg2", help="cfg0..cfg4 (default: cfg2, the 32-layer batch-8 32K case)")
+    ap_.add_argument("--no-cpu-baseline", action="store_true")
+    ap_.add_argument("--no-breakdown", action="store_true")
+    args = ap_.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (instances are independent, "
+              "sharding is described in DESIGN.md but not built).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_04077_amd.runner import DecodeRun
+    from workloads import CONFIGS, kv_cache, predictor_weights, queries
+
+    w = CONFIGS[args.workload]
+    total_steps = args.warmup + args.steps
+    if total_steps > w.steps:
+        w = w.with_(steps=total_steps)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    run = DecodeRun(w, dev)
+    run.set_weights(predictor_weights(w))
+    K, V = kv_cache(w, dev)
+    H = w.hist_len
+    for j in range(H):                                    # prefill tail fills the history
+        run.warmup_calibrate(queries(w, j - H, dev), K, w.t0 - H + 1 + j)
+    qs = [queries(w, s, dev) for s in range(total_steps)]
+    torch.cuda.synchronize()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, run, K, V)
+
+    def one_step(s):
+        run.step(qs[s], K, V, w.t_at(s), calibrate=w.is_calibration_step(s))
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, total_steps):
+        one_step(s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    n_calib = sum(1 for s in range(args.warmup, total_steps) if w.is_calibration_step(s))
+
+    # Per-call durations with events on the launch stream, replaying the same steps un-fused.
+    kern_ms = {}
+    if not args.no_breakdown:
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        names = ["predict", "select", "sparse_decode", "update_history", "calibrate"]
+        marks = {n: [] for n in names}
+        for s in range(args.warmup, total_steps):
+            t = w.t_at(s)
+            nb = run.nb(t)
+            seq = [
+                ("predict", lambda: run.ctx.predict(run.hist, run.n_pushed, nb, run.pred, run.ws)),
+                ("select", lambda: run.ctx.select_topk(run.pred, nb, run.idx, run.cnt, run.ws)),
+                ("sparse_decode", lambda: run.ctx.sparse_decode(qs[s], K, V, t, run.idx, run.cnt, run.out, run.row, run.ws)),
+                ("update_history", lambda: run.ctx.update_history(run.hist, run.n_pushed, run.row)),
+            ]
+            if w.is_calibration_step(s):
+                seq.insert(3, ("calibrate", lambda: run.ctx.calibrate(qs[s], K, t, run.row, run.ws)))
+            for name, fn in seq:
+                a, b = ev(), ev()
+                a.record()
+                fn()
+                b.record()
+                marks[name].append((a, b))
+            run.n_pushed += 1
+        torch.cuda.synchronize()
+        for n in names:
+            if marks[n]:
+                kern_ms[n] = sum(a.elapsed_time(b) for a, b in marks[n]) / len(marks[n])
+
+    t_mid = w.t_at(args.warmup + args.steps // 2)
+    ab = algorithmic_bytes(w, t_mid)
+    af = algorithmic_flops(w, t_mid)
+    roofline = None
+    if kern_ms:
+        step_kernels = {k: v for k, v in kern_ms.items() if k in ("predict", "select", "sparse_decode")}
+        dom = max(step_kernels, key=step_kernels.get)
+        if dom == "predict":
+            ach = af["predict"] * w.n_inst / (kern_ms[dom] * 1e-3) / 1e12
+            roofline = {"kernel": dom, "bound": "alu", "achieved": ach, "peak": FP32_VECTOR_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / FP32_VECTOR_PEAK_TFLOPS, "traffic": None}
+        else:
+            ach = ab[dom] * w.n_inst / (kern_ms[dom] * 1e-3) / 1e9
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        roofline["avg_launch_ms"] = kern_ms[dom]
+    step_bytes = (ab["predict"] + ab["select"] + ab["sparse_decode"]) * w.n_inst
+    out = {
+        "metric": "predict+top-k+sparse-attn decode steps/s at 32K ctx; % HBM peak",
+        "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.kv_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "instances": w.n_inst, "layers": w.layers, "batch": w.batch,
+                   "kv_heads": w.kv_heads, "q_per_kv": w.g, "head_dim": w.head_dim, "context": w.t0,
+                   "block": w.block, "history": w.hist_len, "budget_tokens": w.budget_tokens,
+                   "predictor_channels": [w.c1, w.c2], "calibration_every": w.calib_every,
+                   "calibration_steps_in_timed_region": n_calib},
+        "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_algorithmic_GB": step_bytes / 1e9,
+        "kernel_ms": kern_ms,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
