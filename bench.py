@@ -26,7 +26,8 @@ def algorithmic_bytes(w, t):
     nb = (t + w.block - 1) // w.block
     k = min(w.k_blocks, nb)
     return {
-        "predict": w.hist_len * nb * 4 + nb * 4,
+        "predict_full": w.hist_len * nb * 4 + nb * 4,
+        "predict_incremental": 10 * nb * 4 + 3 * nb * 4,      # 10 history rows, state read + write, pred write
         "select": nb * 4 + k * 4,
         "sparse_decode": 2 * k * w.block * w.head_dim * s_kv + w.g * w.head_dim * (s_kv + 4) + k * 4 + nb * 4,
         "calibrate": t * w.head_dim * s_kv + w.g * w.head_dim * s_kv + nb * 4,
@@ -36,8 +37,11 @@ def algorithmic_bytes(w, t):
 def algorithmic_flops(w, t):
     nb = (t + w.block - 1) // w.block
     k = min(w.k_blocks, nb)
+    y1_row, y2_tap_row = 2 * 9 * w.c1, 2 * 3 * w.c1 * w.c2       # flops per column per y1 row / per (y2 row, tap row)
     return {
-        "predict": 2 * (9 * w.c1 + 9 * w.c1 * w.c2) * w.hist_len * nb + 2 * w.c2 * nb,
+        "predict_full": (y1_row + 3 * y2_tap_row) * w.hist_len * nb + 2 * w.c2 * nb,
+        # 8 y1 rows and 6 y2 rows (two of them with one tap row outside the window) per column
+        "predict_incremental": (8 * y1_row + 16 * y2_tap_row) * nb + 6 * 2 * w.c2 * nb,
         "sparse_decode": 4 * w.g * w.head_dim * k * w.block,
     }
 
@@ -79,8 +83,8 @@ def cpu_baseline(w, run, K, V, budget_s=20.0, max_inst=16):
 def main():
     ap_ = argparse.ArgumentParser()
     ap_.add_argument("--gpus", type=int, default=1)
-    ap_.add_argument("--steps", type=int, default=64)
-    ap_.add_argument("--warmup", type=int, default=4)
+    ap_.add_argument("--steps", type=int, default=512)
+    ap_.add_argument("--warmup", type=int, default=8)
     ap_.add_argument("--workload", default="cfg2", help="cfg0..cfg4 (default: cfg2, the 32-layer batch-8 32K case)")
     ap_.add_argument("--no-cpu-baseline", action="store_true")
     ap_.add_argument("--no-breakdown", action="store_true")
@@ -113,58 +117,70 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, run, K, V)
 
+    modes = []
+
     def one_step(s):
-        run.step(qs[s], K, V, w.t_at(s), calibrate=w.is_calibration_step(s))
+        return run.step(qs[s], K, V, w.t_at(s), calibrate=w.is_calibration_step(s))
 
     for s in range(args.warmup):
         one_step(s)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.warmup, total_steps):
-        one_step(s)
+        modes.append(one_step(s) == 0)       # mode 0 = full-tile re-base
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     n_calib = sum(1 for s in range(args.warmup, total_steps) if w.is_calibration_step(s))
+    n_rebase = sum(modes)
 
     # Per-call durations with events on the launch stream, replaying the same steps un-fused.
     kern_ms = {}
     if not args.no_breakdown:
+        from paper_2502_04077_amd import AP_PRED_ADVANCE, AP_PRED_REBASE
         ev = lambda: torch.cuda.Event(enable_timing=True)
-        names = ["predict", "select", "sparse_decode", "update_history", "calibrate"]
-        marks = {n: [] for n in names}
+        marks = {}
+
+        def timed(name, fn):
+            a, b = ev(), ev()
+            a.record()
+            fn()
+            b.record()
+            marks.setdefault(name, []).append((a, b))
+
         for s in range(args.warmup, total_steps):
             t = w.t_at(s)
             nb = run.nb(t)
-            seq = [
-                ("predict", lambda: run.ctx.predict(run.hist, run.n_pushed, nb, run.pred, run.ws)),
-                ("select", lambda: run.ctx.select_topk(run.pred, nb, run.idx, run.cnt, run.ws)),
-                ("sparse_decode", lambda: run.ctx.sparse_decode(qs[s], K, V, t, run.idx, run.cnt, run.out, run.row, run.ws)),
-                ("update_history", lambda: run.ctx.update_history(run.hist, run.n_pushed, run.row)),
-            ]
+            mode = run._pred_mode(t)
+            pname = {AP_PRED_ADVANCE: "predict_incremental", AP_PRED_REBASE: "predict_full"}.get(mode, "predict_hold")
+            if nb != run.nb(t - 1) and mode == AP_PRED_ADVANCE:
+                pname = "predict_incremental_grow"
+            timed(pname, lambda: run.ctx.predict_incremental(run.hist, run.n_pushed, nb, run.nb(t - 1), mode,
+                                                             run.pstate, run.pred, run.ws))
+            run.state_n, run.state_t = run.n_pushed, t
+            timed("select", lambda: run.ctx.select_topk(run.pred, nb, run.idx, run.cnt, run.ws))
+            timed("sparse_decode", lambda: run.ctx.sparse_decode(qs[s], K, V, t, run.idx, run.cnt, run.out, run.row, run.ws))
             if w.is_calibration_step(s):
-                seq.insert(3, ("calibrate", lambda: run.ctx.calibrate(qs[s], K, t, run.row, run.ws)))
-            for name, fn in seq:
-                a, b = ev(), ev()
-                a.record()
-                fn()
-                b.record()
-                marks[name].append((a, b))
+                timed("calibrate", lambda: run.ctx.calibrate(qs[s], K, t, run.row, run.ws))
+            timed("update_history", lambda: run.ctx.update_history(run.hist, run.n_pushed, run.row))
             run.n_pushed += 1
         torch.cuda.synchronize()
-        for n in names:
-            if marks[n]:
-                kern_ms[n] = sum(a.elapsed_time(b) for a, b in marks[n]) / len(marks[n])
+        for n, m in marks.items():
+            kern_ms[n] = sum(a.elapsed_time(b) for a, b in m) / len(m)
+        kern_ms = {k: round(v, 5) for k, v in kern_ms.items()}
 
     t_mid = w.t_at(args.warmup + args.steps // 2)
     ab = algorithmic_bytes(w, t_mid)
     af = algorithmic_flops(w, t_mid)
     roofline = None
     if kern_ms:
-        step_kernels = {k: v for k, v in kern_ms.items() if k in ("predict", "select", "sparse_decode")}
-        dom = max(step_kernels, key=step_kernels.get)
-        if dom == "predict":
-            ach = af["predict"] * w.n_inst / (kern_ms[dom] * 1e-3) / 1e12
+        per_step = {k: v for k, v in kern_ms.items() if k in ("predict_incremental", "select", "sparse_decode")}
+        if "predict_incremental" not in per_step and "predict_full" in kern_ms:
+            per_step["predict_full"] = kern_ms["predict_full"]
+        dom = max(per_step, key=per_step.get)
+        if dom.startswith("predict"):
+            fl = af[dom] * w.n_inst
+            ach = fl / (kern_ms[dom] * 1e-3) / 1e12
             roofline = {"kernel": dom, "bound": "alu", "achieved": ach, "peak": FP32_VECTOR_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": ach / FP32_VECTOR_PEAK_TFLOPS, "traffic": None}
         else:
@@ -172,7 +188,12 @@ def main():
             roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": ach / HBM_PEAK_GBS, "traffic": None}
         roofline["avg_launch_ms"] = kern_ms[dom]
-    step_bytes = (ab["predict"] + ab["select"] + ab["sparse_decode"]) * w.n_inst
+        hbm_kernel = "sparse_decode"
+        roofline["hbm_kernels"] = {
+            k: {"GB/s": ab[k] * w.n_inst / (kern_ms[k] * 1e-3) / 1e9,
+                "frac": ab[k] * w.n_inst / (kern_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            for k in ("sparse_decode", "calibrate") if k in kern_ms}
+    step_bytes = (ab["predict_incremental"] + ab["select"] + ab["sparse_decode"]) * w.n_inst
     out = {
         "metric": "predict+top-k+sparse-attn decode steps/s at 32K ctx; % HBM peak",
         "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -182,7 +203,8 @@ def main():
                    "kv_heads": w.kv_heads, "q_per_kv": w.g, "head_dim": w.head_dim, "context": w.t0,
                    "block": w.block, "history": w.hist_len, "budget_tokens": w.budget_tokens,
                    "predictor_channels": [w.c1, w.c2], "calibration_every": w.calib_every,
-                   "calibration_steps_in_timed_region": n_calib},
+                   "calibration_steps_in_timed_region": n_calib, "predictor": "incremental",
+                   "predictor_rebase_every": run.rebase_every, "rebase_steps_in_timed_region": n_rebase},
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_GB": step_bytes / 1e9,
         "kernel_ms": kern_ms,

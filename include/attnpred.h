@@ -46,6 +46,11 @@ extern "C" {
 #define AP_F32 0
 #define AP_BF16 1
 
+/* Predictor evaluation modes (ap_predict_incremental, ap_step). */
+#define AP_PRED_REBASE 0  /* evaluate the full H x nb tile; (re)writes pstate if one is given        */
+#define AP_PRED_ADVANCE 1 /* pstate is valid for n_pushed - 1 rows: move it forward by one row       */
+#define AP_PRED_HOLD 2    /* pstate is already valid for n_pushed rows: use it as it is              */
+
 typedef struct ap_ctx ap_ctx; /* opaque host object; owns only the device copy of the weights */
 
 typedef struct ap_config {
@@ -93,6 +98,22 @@ int ap_set_weights(ap_ctx* ctx, const float* host_blob, size_t n_floats, void* s
 int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur, float* pred,
                void* ws, void* stream);
 
+/* The same prediction, evaluated incrementally.  Both convolutions commute with a one-row time
+ * shift except in the first and last two rows, and the head is linear, so the contribution of
+ * rows 2..H-3 is carried in one float per column (pstate) that moves forward by subtracting the row
+ * that leaves those rows and adding the one that enters; only 6 of the H second-layer rows are
+ * evaluated per step.  Equal to ap_predict in real arithmetic; every ADVANCE adds two fp32
+ * roundings per column to pstate, so REBASE every few hundred steps.
+ *   pstate   device float [n_inst][nb_cap], owned by the caller, meaningful only to this library
+ *   mode     AP_PRED_REBASE | AP_PRED_ADVANCE | AP_PRED_HOLD.  ADVANCE must be called exactly once
+ *            per pushed row (it needs the row that left the window, still in the ring's spare slot)
+ *   nb_prev  nb_cur of the call that last wrote pstate (<= nb_cur); columns from nb_prev - 1 on are
+ *            re-evaluated in full when the tile has grown.  Ignored for REBASE.
+ * With hist_len < 6 every mode evaluates the full tile. */
+int ap_predict_incremental(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur,
+                           int32_t nb_prev, int32_t mode, float* pstate, float* pred, void* ws,
+                           void* stream);
+
 /* Algorithm 1 step 5 with the budget split of Sec. 4.1: blocks [0, n_sink) and
  * [nb_cur - n_local, nb_cur) are always selected; the other k - n_sink - n_local go to the
  * highest pred among the blocks in between, equal scores to the lower index (-0 == +0).
@@ -127,11 +148,13 @@ int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float
 int ap_update_history(ap_ctx* ctx, float* hist, int64_t n_pushed, const float* row, void* stream);
 
 /* One fused decode step: predict -> select -> sparse decode -> push, with the pooled row written
- * straight into ring slot n_pushed % R.  Equivalent to the four calls above in that order.
+ * straight into ring slot n_pushed % R.  Equivalent to ap_predict_incremental (ap_predict if pstate
+ * is NULL), ap_select_topk, ap_sparse_decode and ap_update_history in that order, with
+ * nb_prev = ceil((t_cur - 1) / b): decoding appends one token per step.
  * pred, idx and cnt are outputs as in the single calls. */
 int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* K,
             const void* V, int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred,
-            void* ws, void* stream);
+            float* pstate, int32_t pred_mode, void* ws, void* stream);
 
 const char* ap_strerror(int code);
 

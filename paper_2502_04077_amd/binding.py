@@ -15,10 +15,11 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libattnpred.so")
 
 AP_F32, AP_BF16 = 0, 1
+AP_PRED_REBASE, AP_PRED_ADVANCE, AP_PRED_HOLD = 0, 1, 2
 
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights",
-    "ap_predict", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
+    "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
     "ap_strerror",
 ]
 
@@ -59,11 +60,12 @@ def load_library() -> C.CDLL:
     lib.ap_nb_cap.restype = i32
     lib.ap_set_weights.argtypes = [vp, vp, sz, vp]
     lib.ap_predict.argtypes = [vp, vp, i64, i32, vp, vp, vp]
+    lib.ap_predict_incremental.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.ap_select_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.ap_sparse_decode.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ap_calibrate.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.ap_update_history.argtypes = [vp, vp, i64, vp, vp]
-    lib.ap_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.ap_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.ap_strerror.argtypes = [C.c_int]
     lib.ap_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -130,6 +132,10 @@ class Context:
     def predict(self, hist, n_pushed, nb_cur, pred, ws) -> None:
         _check(self._lib.ap_predict(self._h, _ptr(hist), n_pushed, nb_cur, _ptr(pred), _ptr(ws), _stream()))
 
+    def predict_incremental(self, hist, n_pushed, nb_cur, nb_prev, mode, pstate, pred, ws) -> None:
+        _check(self._lib.ap_predict_incremental(self._h, _ptr(hist), n_pushed, nb_cur, nb_prev, mode, _ptr(pstate),
+                                                _ptr(pred), _ptr(ws), _stream()))
+
     def select_topk(self, pred, nb_cur, idx, cnt, ws) -> None:
         _check(self._lib.ap_select_topk(self._h, _ptr(pred), nb_cur, _ptr(idx), _ptr(cnt), _ptr(ws), _stream()))
 
@@ -143,6 +149,7 @@ class Context:
     def update_history(self, hist, n_pushed, row) -> None:
         _check(self._lib.ap_update_history(self._h, _ptr(hist), n_pushed, _ptr(row), _stream()))
 
-    def step(self, hist, n_pushed, q, K, V, t_cur, out, idx, cnt, pred, ws) -> None:
+    def step(self, hist, n_pushed, q, K, V, t_cur, out, idx, cnt, pred, pstate, pred_mode, ws) -> None:
         _check(self._lib.ap_step(self._h, _ptr(hist), n_pushed, _ptr(q), _ptr(K), _ptr(V), t_cur, _ptr(out),
-                                 _ptr(idx), _ptr(cnt), _ptr(pred), _ptr(ws), _stream()))
+                                 _ptr(idx), _ptr(cnt), _ptr(pred), None if pstate is None else _ptr(pstate),
+                                 pred_mode, _ptr(ws), _stream()))

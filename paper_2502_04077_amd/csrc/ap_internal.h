@@ -43,8 +43,12 @@ struct WsLayout {
 WsLayout ws_layout(const Shape& s);
 
 // Launchers.  Each returns hipSuccess or the launch error.
+// Full-tile predictor over columns [col_begin, nb_cur); also writes the interior state if pstate != null.
 hipError_t launch_predict(const Shape& s, const float* dweights, const float* hist, int newest_slot,
-                          int nb_cur, float* pred, hipStream_t st);
+                          int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st);
+// Incremental predictor over all columns; advance != 0 moves the state forward by one pushed row first.
+hipError_t launch_predict_inc(const Shape& s, const float* dweights, const float* hist, int newest_slot,
+                              int nb_cur, int advance, float* pstate, float* pred, hipStream_t st);
 hipError_t launch_select(const Shape& s, const float* pred, int nb_cur, int32_t* idx, int32_t* cnt,
                          hipStream_t st);
 // row_stride: floats between consecutive instances' rows (nb_cap for a plain row buffer,

@@ -149,6 +149,28 @@ static int newest_slot_of(const Shape& s, int64_t n_pushed) {
   return n_pushed <= 0 ? s.R - 1 : (int)((n_pushed - 1) % s.R);
 }
 
+// Runs the predictor in the requested mode; shared by ap_predict_incremental and ap_step.
+static int run_predictor(const ap_ctx* ctx, const float* hist, int64_t n_pushed, int nb_cur, int nb_prev, int mode,
+                         float* pstate, float* pred, hipStream_t st) {
+  const Shape& s = ctx->s;
+  const int newest = newest_slot_of(s, n_pushed);
+  if (pstate == nullptr || mode == AP_PRED_REBASE || s.H < 6) {
+    return ap::launch_predict(s, ctx->dweights, hist, newest, nb_cur, 0, pstate, pred, st) == hipSuccess ? AP_OK
+                                                                                                          : AP_ERR_HIP;
+  }
+  if (ap::launch_predict_inc(s, ctx->dweights, hist, newest, nb_cur, mode == AP_PRED_ADVANCE, pstate, pred, st) !=
+      hipSuccess)
+    return AP_ERR_HIP;
+  if (nb_cur > nb_prev) {
+    // The tile grew: column nb_prev - 1 gained a right neighbour inside the tile and the new columns
+    // have no state yet; evaluate those columns in full.
+    const int col_begin = nb_prev > 1 ? nb_prev - 1 : 0;
+    if (ap::launch_predict(s, ctx->dweights, hist, newest, nb_cur, col_begin, pstate, pred, st) != hipSuccess)
+      return AP_ERR_HIP;
+  }
+  return AP_OK;
+}
+
 int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur, float* pred, void* ws,
                void* stream) {
   if (ctx == nullptr) return AP_ERR_ARG;
@@ -156,9 +178,20 @@ int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur,
   const Shape& s = ctx->s;
   if (!ctx->have_weights) return AP_ERR_STATE;
   if (n_pushed < 0 || nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
-  hipError_t e = ap::launch_predict(s, ctx->dweights, hist, newest_slot_of(s, n_pushed), nb_cur, pred,
-                                    static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+  return run_predictor(ctx, hist, n_pushed, nb_cur, nb_cur, AP_PRED_REBASE, nullptr, pred,
+                       static_cast<hipStream_t>(stream));
+}
+
+int ap_predict_incremental(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur, int32_t nb_prev,
+                           int32_t mode, float* pstate, float* pred, void* ws, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(pstate); AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (!ctx->have_weights) return AP_ERR_STATE;
+  if (mode != AP_PRED_REBASE && mode != AP_PRED_ADVANCE && mode != AP_PRED_HOLD) return AP_ERR_ARG;
+  if (n_pushed < 0 || nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
+  if (mode != AP_PRED_REBASE && (nb_prev < 1 || nb_prev > nb_cur)) return AP_ERR_RANGE;
+  return run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, mode, pstate, pred, static_cast<hipStream_t>(stream));
 }
 
 int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx, int32_t* cnt, void* ws,
@@ -202,17 +235,21 @@ int ap_update_history(ap_ctx* ctx, float* hist, int64_t n_pushed, const float* r
 }
 
 int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* K, const void* V,
-            int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred, void* ws, void* stream) {
+            int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred, float* pstate, int32_t pred_mode,
+            void* ws, void* stream) {
   if (ctx == nullptr) return AP_ERR_ARG;
   AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(V); AP_REQUIRE_PTR(out);
   AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt); AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(ws);
+  if (pstate != nullptr && !aligned16(pstate)) return AP_ERR_ALIGN;
   const Shape& s = ctx->s;
   if (!ctx->have_weights) return AP_ERR_STATE;
+  if (pred_mode != AP_PRED_REBASE && pred_mode != AP_PRED_ADVANCE && pred_mode != AP_PRED_HOLD) return AP_ERR_ARG;
   if (n_pushed < 0 || t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
   const int nb_cur = (t_cur + s.b - 1) / s.b;
+  const int nb_prev = t_cur > 1 ? (t_cur - 1 + s.b - 1) / s.b : 1;   // one token is appended per step
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (ap::launch_predict(s, ctx->dweights, hist, newest_slot_of(s, n_pushed), nb_cur, pred, st) != hipSuccess)
-    return AP_ERR_HIP;
+  int rc = run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, pred_mode, pstate, pred, st);
+  if (rc != AP_OK) return rc;
   if (ap::launch_select(s, pred, nb_cur, idx, cnt, st) != hipSuccess) return AP_ERR_HIP;
   const int slot = (int)(n_pushed % s.R);
   float* slot_row = hist + (size_t)slot * s.nb_cap;

@@ -7,12 +7,19 @@ from __future__ import annotations
 
 import torch
 
-from .binding import Context
+from .binding import AP_PRED_ADVANCE, AP_PRED_HOLD, AP_PRED_REBASE, Context
 
 
 class DecodeRun:
-    def __init__(self, w, device="cuda:0"):
+    def __init__(self, w, device="cuda:0", incremental=True, rebase_every=512):
+        """incremental: carry the predictor's interior state across steps (ap_predict_incremental)
+        and re-evaluate the full tile every `rebase_every` pushes; False evaluates the full tile
+        on every step."""
         self.w = w
+        self.incremental = incremental
+        self.rebase_every = rebase_every
+        self.state_n = None       # n_pushed the predictor state is valid for
+        self.state_t = None       # t_cur of the call that wrote it
         self.dev = torch.device(device)
         self.ctx = Context(n_inst=w.n_inst, g=w.g, head_dim=w.head_dim, block=w.block, hist_len=w.hist_len,
                            t_cap=w.t_cap, k_blocks=w.k_blocks, n_sink=w.n_sink, n_local=w.n_local,
@@ -22,6 +29,7 @@ class DecodeRun:
         f32, i32 = torch.float32, torch.int32
         self.hist = torch.zeros((w.n_inst, R, nbc), dtype=f32, device=self.dev)
         self.pred = torch.zeros((w.n_inst, nbc), dtype=f32, device=self.dev)
+        self.pstate = torch.zeros((w.n_inst, nbc), dtype=f32, device=self.dev)
         self.row = torch.zeros((w.n_inst, nbc), dtype=f32, device=self.dev)
         self.idx = torch.zeros((w.n_inst, w.k_blocks), dtype=i32, device=self.dev)
         self.cnt = torch.zeros((w.n_inst,), dtype=i32, device=self.dev)
@@ -51,19 +59,44 @@ class DecodeRun:
         self.ctx.update_history(self.hist, self.n_pushed, self.row)
         self.n_pushed += 1
 
+    def _pred_mode(self, t):
+        """Which predictor mode is valid now, and the bookkeeping for the next call."""
+        if not self.incremental:
+            return AP_PRED_REBASE
+        n = self.n_pushed
+        if self.state_n == n and self.state_t == t:
+            mode = AP_PRED_HOLD
+        elif self.state_n == n - 1 and self.state_t == t - 1 and n % self.rebase_every != 0:
+            mode = AP_PRED_ADVANCE
+        else:
+            mode = AP_PRED_REBASE
+        return mode
+
     def step_unfused(self, q, K, V, t, calibrate=False):
         nb = self.nb(t)
-        self.ctx.predict(self.hist, self.n_pushed, nb, self.pred, self.ws)
+        mode = self._pred_mode(t)
+        if self.incremental:
+            self.ctx.predict_incremental(self.hist, self.n_pushed, nb, self.nb(max(t - 1, 1)), mode, self.pstate,
+                                         self.pred, self.ws)
+            self.state_n, self.state_t = self.n_pushed, t
+        else:
+            self.ctx.predict(self.hist, self.n_pushed, nb, self.pred, self.ws)
         self.ctx.select_topk(self.pred, nb, self.idx, self.cnt, self.ws)
         self.ctx.sparse_decode(q, K, V, t, self.idx, self.cnt, self.out, self.row, self.ws)
         if calibrate:
             self.ctx.calibrate(q, K, t, self.row, self.ws)
         self.ctx.update_history(self.hist, self.n_pushed, self.row)
         self.n_pushed += 1
+        return mode
 
     def step(self, q, K, V, t, calibrate=False):
-        self.ctx.step(self.hist, self.n_pushed, q, K, V, t, self.out, self.idx, self.cnt, self.pred, self.ws)
+        mode = self._pred_mode(t)
+        self.ctx.step(self.hist, self.n_pushed, q, K, V, t, self.out, self.idx, self.cnt, self.pred,
+                      self.pstate if self.incremental else None, mode, self.ws)
+        if self.incremental:
+            self.state_n, self.state_t = self.n_pushed, t
         if calibrate:
             self.ctx.calibrate(q, K, t, self.row, self.ws)
             self.ctx.update_history(self.hist, self.n_pushed, self.row)
         self.n_pushed += 1
+        return mode

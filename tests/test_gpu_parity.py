@@ -140,6 +140,58 @@ def test_predict_vs_oracle(H, nb, c1, c2, pushed):
         assert np.all(got[i, nb:] == -5.0)
 
 
+@pytest.mark.parametrize("H,nb0,c1,c2,n_steps,grow_every", [
+    (16, 130, 8, 8, 60, 5), (64, 200, 8, 8, 150, 16), (6, 70, 4, 4, 40, 3), (64, 65, 16, 32, 70, 0),
+    (16, 1, 8, 8, 40, 4), (5, 40, 8, 8, 12, 0),
+])
+def test_predict_incremental_tracks_oracle(H, nb0, c1, c2, n_steps, grow_every):
+    """ADVANCE once per pushed row (no re-base in between), tile growing, ring wrapping: every
+    prediction must match the oracle's full evaluation of the same history; HOLD repeats it bit for bit."""
+    dev = _dev()
+    ap = _ap()
+    n_inst, b = 2, 16
+    nb_cap = nb0 + (n_steps // grow_every if grow_every else 0) + 4
+    ctx = ap.Context(n_inst=n_inst, g=1, head_dim=64, block=b, hist_len=H, t_cap=nb_cap * b, k_blocks=4,
+                     n_sink=1, n_local=1, c1=c1, c2=c2, kv_dtype="f32")
+    R = ctx.hist_slots()
+    rng = np.random.default_rng(H * 31 + nb0)
+    blob = (rng.standard_normal(n_weight_floats(c1, c2)) * 0.2).astype(np.float32)
+    ctx.set_weights(blob)
+    wts = orc.PredictorWeights.from_blob(blob, c1, c2)
+    hist = torch.zeros((n_inst, R, nb_cap), dtype=torch.float32, device=dev)
+    row = torch.zeros((n_inst, nb_cap), dtype=torch.float32, device=dev)
+    pred = torch.zeros((n_inst, nb_cap), dtype=torch.float32, device=dev)
+    pstate = torch.full((n_inst, nb_cap), 123.0, dtype=torch.float32, device=dev)
+    ws = torch.zeros((max(16, ctx.workspace_bytes()),), dtype=torch.uint8, device=dev)
+    logical = np.zeros((n_inst, H, nb_cap))
+    nb, nb_prev, worst = nb0, nb0, 0.0
+    for n in range(n_steps):
+        mode = ap.AP_PRED_REBASE if n == 0 else ap.AP_PRED_ADVANCE
+        ctx.predict_incremental(hist, n, nb, nb_prev, mode, pstate, pred, ws)
+        torch.cuda.synchronize()
+        got = pred.cpu().numpy().copy()
+        if n % 7 == 3:
+            ctx.predict_incremental(hist, n, nb, nb, ap.AP_PRED_HOLD, pstate, pred, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(pred.cpu().numpy()[:, :nb], got[:, :nb]), f"HOLD changed the prediction at n={n}"
+        if n < 3 * H or n % 5 == 0 or n == n_steps - 1:
+            for i in range(n_inst):
+                ref = orc.predict(logical[i], nb, wts)
+                assert_close(got[i, :nb], ref, f"n={n} inst {i} nb={nb}")
+                worst = max(worst, np.abs(got[i, :nb] - ref).max() / np.abs(ref).max())
+        # push a new row of the current width, then maybe grow the tile for the next call
+        r = np.zeros((n_inst, nb_cap), dtype=np.float32)
+        r[:, :nb] = (rng.random((n_inst, nb)) ** 4).astype(np.float32)
+        row.copy_(torch.from_numpy(r))
+        ctx.update_history(hist, n, row)
+        for i in range(n_inst):
+            logical[i] = orc.history_push(logical[i], r[i].astype(np.float64))
+        nb_prev = nb
+        if grow_every and (n + 1) % grow_every == 0:
+            nb += 1
+    print(f"incremental predictor worst relative error over {n_steps} un-rebased steps: {worst:.2e}")
+
+
 # --------------------------------------------------------------------------------------------- attention
 ATTN_CASES = [
     # name, kwargs, t_cur, n_inst hint
@@ -264,9 +316,10 @@ def test_update_history_ring_is_a_fifo():
 
 
 # --------------------------------------------------------------------------------------------- whole steps
-def lockstep(w, dev, steps, sample, fused_every=2):
+def lockstep(w, dev, steps, sample, fused_every=2, incremental=True):
     """Runs decode steps on the GPU; at each step the oracle starts from the GPU's own history."""
     run = _run(w, dev)
+    run.incremental = incremental
     K, V = kv_cache(w, dev)
     wts = orc.PredictorWeights.from_blob(predictor_weights(w), w.c1, w.c2)
     H, b = w.hist_len, w.block
@@ -330,6 +383,13 @@ def test_lockstep_cfg0_all_steps():
     st = lockstep(w, dev, w.steps, sample=[0], fused_every=2)
     print("cfg0 lock-step:", st)
     assert st["checked"] == w.steps
+
+
+def test_lockstep_cfg0_full_tile_predictor():
+    dev = _dev()
+    w = CONFIGS["cfg0"]
+    st = lockstep(w, dev, 10, sample=[0], fused_every=2, incremental=False)
+    assert st["checked"] == 10
 
 
 def test_lockstep_small_bf16_block_boundary():
