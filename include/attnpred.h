@@ -46,6 +46,11 @@ extern "C" {
 #define AP_F32 0
 #define AP_BF16 1
 
+/* ap_config.flags */
+#define AP_FLAG_PREDICTOR_FP32 1 /* keep the incremental predictor's second conv layer in fp32 FMAs.
+                                    Default for 8/8 channels: f16 operands on MFMA with fp32
+                                    accumulation (pred moves by ~1e-5 of its magnitude).            */
+
 /* Predictor evaluation modes (ap_predict_incremental, ap_step). */
 #define AP_PRED_REBASE 0  /* evaluate the full H x nb tile; (re)writes pstate if one is given        */
 #define AP_PRED_ADVANCE 1 /* pstate is valid for n_pushed - 1 rows: move it forward by one row       */
@@ -65,6 +70,7 @@ typedef struct ap_config {
   int32_t n_local;  /* forced trailing blocks (Sec. 4.1: local tokens are part of the budget)       */
   int32_t c1, c2;   /* predictor channels; compiled pairs: (4,4) (8,8) (16,32)                      */
   int32_t kv_dtype; /* AP_F32 or AP_BF16: dtype of q, K and V                                       */
+  int32_t flags;    /* 0 or a combination of AP_FLAG_*                                              */
 } ap_config;
 
 /* Validates the configuration and creates a context (host object only, no device work).

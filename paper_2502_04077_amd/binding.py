@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libattnpre
 
 AP_F32, AP_BF16 = 0, 1
 AP_PRED_REBASE, AP_PRED_ADVANCE, AP_PRED_HOLD = 0, 1, 2
+AP_FLAG_PREDICTOR_FP32 = 1
 
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights",
@@ -27,7 +28,7 @@ EXPORTS = [
 class ap_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_inst", "g", "head_dim", "block", "hist_len", "t_cap", "k_blocks", "n_sink", "n_local",
-        "c1", "c2", "kv_dtype")]
+        "c1", "c2", "kv_dtype", "flags")]
 
 
 class ApError(RuntimeError):
@@ -94,10 +95,10 @@ class Context:
     """Owns one ap_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, *, n_inst, g, head_dim, block, hist_len, t_cap, k_blocks, n_sink, n_local, c1, c2,
-                 kv_dtype):
+                 kv_dtype, flags=0):
         lib = load_library()
         self.cfg = ap_config(n_inst, g, head_dim, block, hist_len, t_cap, k_blocks, n_sink, n_local, c1, c2,
-                             AP_BF16 if kv_dtype in ("bf16", AP_BF16) else AP_F32)
+                             AP_BF16 if kv_dtype in ("bf16", AP_BF16) else AP_F32, flags)
         h = C.c_void_p()
         _check(lib.ap_create(C.byref(self.cfg), C.byref(h)))
         self._h = h

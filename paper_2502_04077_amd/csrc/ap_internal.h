@@ -25,6 +25,7 @@ constexpr int kCalibChunkTokens = 1024;       // tokens per calibration workgrou
 //   b3                         at 10*c1 + 9*c1*c2 + 2*c2
 struct Shape {
   int n_inst, g, d, b, H, R, t_cap, nb_cap, k, n_sink, n_local, c1, c2, kv_dtype;
+  int predictor_mfma; // second conv layer of the incremental predictor on f16 MFMA (8/8 channels only)
   int n_split;        // workgroups per instance in sparse decode
   int calib_chunks;   // max workgroups per instance in calibrate
 };
@@ -41,6 +42,21 @@ struct WsLayout {
 };
 
 WsLayout ws_layout(const Shape& s);
+
+// Incremental predictor: kernel row kh through which staged y1 row q feeds output `out` of half `half`
+// (0 = top: leaving row, row 0, row 1; 1 = bottom: entering row, row H-2, row H-1), or -1 if unused.
+__host__ __device__ constexpr int predictor_tap(int half, int out, int q) {
+  constexpr int T[2][3][4] = {{{0, 1, 2, -1}, {-1, 2, -1, 1}, {-1, 1, 2, 0}},
+                              {{0, 1, 2, -1}, {-1, 0, 1, 2}, {-1, -1, 0, 1}}};
+  return T[half][out][q];
+}
+
+// f16 operand table of the MFMA predictor variant (8/8 channels), built on the host by ap_set_weights:
+// [half 2][K-step 6][lane 64][8 f16], placed kMfmaTableFloatOffset floats into the weight buffer
+// (the fp32 section is 10*8 + 9*64 + 2*8 + 1 = 673 floats; 676 keeps 16-byte alignment).
+// It is followed by the layer-1 table [half 2][lane 64][8 f16]: row m = 8 q + c1, K slot k = 3 * xrow + kw.
+constexpr int kMfmaTableFloatOffset = 676;
+constexpr int kMfmaTableHalfs = 2 * 6 * 64 * 8 + 2 * 64 * 8;
 
 // Launchers.  Each returns hipSuccess or the launch error.
 // Full-tile predictor over columns [col_begin, nb_cur); also writes the interior state if pstate != null.

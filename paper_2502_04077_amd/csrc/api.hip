@@ -79,6 +79,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   s.n_inst = c->n_inst; s.g = c->g; s.d = c->head_dim; s.b = c->block; s.H = c->hist_len;
   s.R = c->hist_len + 1; s.t_cap = c->t_cap; s.nb_cap = c->t_cap / c->block; s.k = c->k_blocks;
   s.n_sink = c->n_sink; s.n_local = c->n_local; s.c1 = c->c1; s.c2 = c->c2; s.kv_dtype = c->kv_dtype;
+  s.predictor_mfma = (c->c1 == 8 && c->c2 == 8 && !(c->flags & AP_FLAG_PREDICTOR_FP32)) ? 1 : 0;
   s.n_split = ap::choose_split(s);
   const int chunk_blocks = ap::kCalibChunkTokens / s.b;
   s.calib_chunks = (s.nb_cap + chunk_blocks - 1) / chunk_blocks;
@@ -116,7 +117,9 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   const float* b2 = w2 + 9 * (size_t)c1 * c2;
   const float* w3 = b2 + c2;
   const float* b3 = w3 + c2;
-  std::vector<float> packed(expect);
+  const bool mfma_table = (c1 == 8 && c2 == 8);
+  const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + ap::kMfmaTableHalfs / 2 : expect;
+  std::vector<float> packed(total, 0.f);
   float* p = packed.data();
   for (int t = 0; t < 9; ++t)
     for (int c = 0; c < c1; ++c) p[t * c1 + c] = w1[c * 9 + t];
@@ -132,13 +135,47 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   for (int c = 0; c < c2; ++c) p[c] = w3[c];
   p += c2;
   p[0] = b3[0];
+  if (mfma_table) {
+    // A operand of the 32x32x16 f16 MFMA: lane (m = lane % 32, h = lane / 32) of K-step s holds the 8
+    // input channels of K chunk 2s + h = (q, kw) for row m = 8 * out + c2 (rows 24..31 stay zero).
+    _Float16* t = reinterpret_cast<_Float16*>(packed.data() + ap::kMfmaTableFloatOffset);
+    for (int half = 0; half < 2; ++half)
+      for (int s = 0; s < 6; ++s)
+        for (int lane = 0; lane < 64; ++lane) {
+          const int m = lane % 32, chunk = 2 * s + lane / 32, q = chunk / 3, kw = chunk % 3;
+          for (int ci = 0; ci < 8; ++ci) {
+            float v = 0.f;
+            if (m < 24) {
+              const int kh = ap::predictor_tap(half, m / 8, q);
+              if (kh >= 0) v = w2[(((size_t)(m % 8) * c1 + ci) * 3 + kh) * 3 + kw];
+            }
+            t[((half * 6 + s) * 64 + lane) * 8 + ci] = (_Float16)v;
+          }
+        }
+    // Layer 1: lane (m = 8 q + c, h) holds K slots k = 8 h + e = 3 * xrow + kw over the five staged x rows.
+    // y1 row q of a half reads staged rows base .. base + 2; a tap row outside the history window is dropped.
+    _Float16* t1 = t + 2 * 6 * 64 * 8;
+    for (int half = 0; half < 2; ++half)
+      for (int lane = 0; lane < 64; ++lane)
+        for (int e = 0; e < 8; ++e) {
+          const int m = lane % 32, k = 8 * (lane / 32) + e, q = m / 8, c = m % 8;
+          const int base = (half == 0 && q == 3) ? 0 : q;
+          const int zero_kh = q == 3 ? (half == 0 ? 0 : 2) : -1;
+          float v = 0.f;
+          if (k < 15) {
+            const int kh = k / 3 - base, kw = k % 3;
+            if (kh >= 0 && kh < 3 && kh != zero_kh) v = w1[(c * 3 + kh) * 3 + kw];
+          }
+          t1[(half * 64 + lane) * 8 + e] = (_Float16)v;
+        }
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->dweights == nullptr &&
-      hipMalloc(reinterpret_cast<void**>(&ctx->dweights), expect * sizeof(float)) != hipSuccess) {
+      hipMalloc(reinterpret_cast<void**>(&ctx->dweights), total * sizeof(float)) != hipSuccess) {
     ctx->dweights = nullptr;
     return AP_ERR_HIP;
   }
-  if (hipMemcpyAsync(ctx->dweights, packed.data(), expect * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess)
+  if (hipMemcpyAsync(ctx->dweights, packed.data(), total * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess)
     return AP_ERR_HIP;
   if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;   // `packed` dies on return
   ctx->have_weights = true;

@@ -170,16 +170,84 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Incremental kernel.  IW output columns per workgroup, 2 * IW threads: threads [0, IW) ("top") evaluate
-// the row leaving the interior and border rows 0, 1; threads [IW, 2 IW) ("bottom") the row entering the
-// interior and border rows H-2, H-1.  Each half stages 5 x rows and 4 y1 rows:
-//   top    x rows -1..3     y1: q0 = interior formula on x[-1..1]   (row 1 of the previous step's window)
-//                               q1 = y1[0] (nothing above the window), q2 = y1[1], q3 = y1[2]
-//          y2: leaving = (q0,q2,q3)   row0 = (-,q1,q2)   row1 = (q1,q2,q3)            [taps kh = 0,1,2]
-//   bottom x rows H-5..H-1  y1: q0 = y1[H-4], q1 = y1[H-3], q2 = y1[H-2], q3 = y1[H-1] (nothing below)
-//          y2: entering = row H-3 = (q0,q1,q2)   row H-2 = (q1,q2,q3)   row H-1 = (q2,q3,-)
-// The leaving row is evaluated by the same instruction sequence, on the same x values, as when it
-// entered, so the two cancel exactly and only the additions into `state` round.
+// Incremental kernel.  IW output columns per workgroup, 2 * IW threads; the first half of the waves
+// ("top") evaluates the row leaving the interior and border rows 0, 1, the second half ("bottom") the
+// row entering the interior and border rows H-2, H-1.  Each half stages 5 x rows and 4 y1 rows q0..q3:
+//   top    x rows -1..3     q0 = y1 formula on x[-1..1] (row 1 of the previous step's window),
+//                           q1 = y1[1], q2 = y1[2], q3 = y1[0] (nothing above the window)
+//   bottom x rows H-5..H-1  q0 = y1[H-4], q1 = y1[H-3], q2 = y1[H-2], q3 = y1[H-1] (nothing below)
+// and three y2 outputs o0..o2, each the sum over kernel rows kh of (w2 row kh) applied to one q:
+//   top    o0 = leaving  row: kh 0,1,2 <- q0,q1,q2    o1 = row 0:   kh 1,2 <- q3,q1     o2 = row 1:   kh 0,1,2 <- q3,q1,q2
+//   bottom o0 = entering row: kh 0,1,2 <- q0,q1,q2    o1 = row H-2: kh 0,1,2 <- q1,q2,q3  o2 = row H-1: kh 0,1 <- q2,q3
+// o0 has the same operand positions in both halves, so the leaving row is evaluated by the same
+// instruction sequence on the same values as when it entered: the two cancel exactly and only the
+// two additions into `state` round.
+//
+// Two variants:
+//   VALU  fp32 FMAs, weights through scalar loads (any compiled channel pair);
+//   MFMA  (C1 = C2 = 8) both layers as 32x32x16 f16 MFMA chains with fp32 accumulation, 32 columns at
+//         a time; see predict_inc_mfma_kernel.
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+template <int C1, int C2, int HF>
+__device__ inline void y2_valu(const Weights<C1, C2>& W, const float* yb, int YW, float (&o)[3][C2]) {
+#pragma unroll
+  for (int k = 0; k < 3; ++k)
+#pragma unroll
+    for (int c = 0; c < C2; ++c) o[k][c] = W.b2[c];
+#pragma unroll 1
+  for (int ci = 0; ci < C1; ++ci) {
+    const_f32_ptr wc = W.w2r + ci * 9 * C2;
+    float y[4][3];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) y[q][kw] = yb[(q * C1 + ci) * YW + kw];
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (predictor_tap(HF, k, q) == kh) {
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw)
+#pragma unroll
+              for (int c = 0; c < C2; ++c) o[k][c] = fmaf(wc[(kh * 3 + kw) * C2 + c], y[q][kw], o[k][c]);
+          }
+  }
+}
+
+// Stages x rows -1..3 (half 0) and H-5..H-1 (half 1), columns c0-2 .. c0-2+XW-1, zero outside the tile.
+template <int XW, int NW>
+__device__ inline void stage_x_rows(float* s_x, const float* hist_inst, int newest_slot, int H, int R, int nb_cap,
+                                    int nb_cur, int c0) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  for (int rr = wave; rr < 10; rr += NW) {
+    const int hf = rr / 5, xr = rr - hf * 5;
+    const int r = hf == 0 ? xr - 1 : H - 5 + xr;
+    const float* src = hist_inst + (size_t)ring_slot(newest_slot, H, R, r) * nb_cap;
+    for (int xc = lane; xc < XW; xc += kWave) {
+      const int j = c0 - 2 + xc;
+      s_x[rr * XW + xc] = (j >= 0 && j < nb_cur) ? src[j] : 0.f;
+    }
+  }
+}
+
+// Writes state and pred for column c0 + tid from the four head-weighted partial sums in s_red[2][2][LD].
+template <int LD>
+__device__ inline void finish_column(const float* s_red, int tid, size_t o, int advance, float b3, int H,
+                                     float* pstate, float* pred) {
+  float st = pstate[o];
+  if (advance) {
+    st = (st - s_red[0 * LD + tid]) + s_red[2 * LD + tid];
+    pstate[o] = st;
+  }
+  pred[o] = b3 + (st + (s_red[1 * LD + tid] + s_red[3 * LD + tid])) / (float)H;
+}
+
 template <int C1, int C2, int IW>
 __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __restrict__ hist,
                                                              const float* __restrict__ wts_global, int R, int H,
@@ -187,33 +255,23 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
                                                              float* __restrict__ pstate, float* __restrict__ pred) {
   constexpr int XW = IW + 4, YW = IW + 2, NT = 2 * IW;
   extern __shared__ __align__(16) float smem[];
-  float* s_x = smem;                        // [2][5][XW]
-  float* s_y1 = s_x + 2 * 5 * XW;           // [2][4][C1][YW]
-  float* s_red = s_y1 + 2 * 4 * C1 * YW;    // [2][2][IW]
+  float* s_y1 = smem;                       // [2][4][C1][YW]
+  float* s_x = s_y1 + 2 * 4 * C1 * YW;      // [2][5][XW]
+  float* s_red = s_x + 2 * 5 * XW;          // [2][2][IW]
   const Weights<C1, C2> W(wts_global);
 
   const int inst = blockIdx.y;
   const int c0 = blockIdx.x * IW;
   const int tid = threadIdx.x;
-  const float* hist_inst = hist + (size_t)inst * R * nb_cap;
-
-  for (int e = tid; e < 2 * 5 * XW; e += NT) {
-    const int hf = e / (5 * XW), rem = e - hf * 5 * XW;
-    const int xr = rem / XW, xc = rem - xr * XW;
-    const int r = hf == 0 ? xr - 1 : H - 5 + xr;
-    const int j = c0 - 2 + xc;
-    float v = 0.f;
-    if (j >= 0 && j < nb_cur) v = hist_inst[(size_t)ring_slot(newest_slot, H, R, r) * nb_cap + j];
-    s_x[e] = v;
-  }
+  stage_x_rows<XW, NT / kWave>(s_x, hist + (size_t)inst * R * nb_cap, newest_slot, H, R, nb_cap, nb_cur, c0);
   __syncthreads();
-  for (int e = tid; e < 2 * 4 * YW; e += NT) {
-    const int hf = e / (4 * YW), rem = e - hf * 4 * YW;
-    const int q = rem / YW, yc = rem - q * YW;
+  // y1: thread (half, column) evaluates its four rows q0..q3; the two halo columns of each (half, q) are
+  // done by 16 threads in a second pass.
+  auto y1_at = [&](int hf, int q, int yc) {
     const int j = c0 - 1 + yc;
-    // first x row of the 3-row window, and which tap row lies outside the history window
-    const int base = hf == 0 ? (q <= 1 ? 0 : q - 1) : q;
-    const int zero_kh = hf == 0 ? (q == 1 ? 0 : -1) : (q == 3 ? 2 : -1);
+    // first staged x row of the 3-row window, and the tap row that lies outside the history window
+    const int base = (hf == 0 && q == 3) ? 0 : q;
+    const int zero_kh = q == 3 ? (hf == 0 ? 0 : 2) : -1;
     const float* xs = s_x + hf * 5 * XW;
     float x[3][3];
 #pragma unroll
@@ -221,92 +279,211 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
 #pragma unroll
       for (int kw = 0; kw < 3; ++kw) x[kh][kw] = (kh == zero_kh) ? 0.f : xs[(base + kh) * XW + yc + kw];
     y1_pixel<C1, C2>(W, x, j >= 0 && j < nb_cur, s_y1 + ((hf * 4 + q) * C1) * YW + yc, YW);
+  };
+  {
+    const int hf = tid / IW, yc = tid - hf * IW;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) y1_at(hf, q, yc);
+    if (tid < 16) y1_at(tid >> 3, (tid >> 1) & 3, IW + (tid & 1));
   }
+  __syncthreads();
+  {
+    const int hf = tid / IW, col = tid - hf * IW;
+    float o[3][C2];
+    const float* yb = s_y1 + (size_t)(hf * 4 * C1) * YW + col;
+    if (hf == 0) y2_valu<C1, C2, 0>(W, yb, YW, o); else y2_valu<C1, C2, 1>(W, yb, YW, o);
+    float moving = 0.f, b1sum = 0.f, b2sum = 0.f;   // head-weighted: the moving row, the two border rows
+#pragma unroll
+    for (int c = 0; c < C2; ++c) {
+      moving = fmaf(W.w3[c], fmaxf(o[0][c], 0.f), moving);
+      b1sum = fmaf(W.w3[c], fmaxf(o[1][c], 0.f), b1sum);
+      b2sum = fmaf(W.w3[c], fmaxf(o[2][c], 0.f), b2sum);
+    }
+    s_red[(hf * 2 + 0) * IW + col] = moving;
+    s_red[(hf * 2 + 1) * IW + col] = b1sum + b2sum;
+  }
+  __syncthreads();
+  if (tid < IW && c0 + tid < nb_cur)
+    finish_column<IW>(s_red, tid, (size_t)inst * nb_cap + c0 + tid, advance, W.b3[0], H, pstate, pred);
+}
+
+// MFMA variant for 8/8 channels.  126 output columns per workgroup, 4 waves: waves 0,1 are the top half,
+// waves 2,3 the bottom half; each wave owns two 32-column blocks.  v_mfma_f32_32x32x16_f16 computes
+// D[32 x 32] += A[32 x 16] * B[16 x 32]; lane l supplies row/column l % 32 and K entries 8 (l / 32) .. + 7, and
+// receives D rows 8 (v / 4) + 4 (l / 32) + v % 4 (v = 0..15) of column l % 32.
+//   layer 1: rows = (q, c1) (all 32 used), K = 16 = (x row 0..4, kw 0..2) + one unused slot, columns = 32
+//            y1 columns.  x is scaled by 2^12 and split into f16 hi + lo (two MFMAs), so tiny probabilities
+//            keep full precision; the weights are f16 (A table built on the host, zero where a tap row falls
+//            outside the history window).  y1 = relu(acc * 2^-12 + b1), zeroed outside the tile, is rounded
+//            to f16 and stored as [q][column][8 channels].
+//   layer 2: rows = (output o, c2) (24 used), K = 96 = (q, kw, c1) in six steps, columns = 32 output columns;
+//            the B operand of a step is one 16-byte LDS read.  Accumulators start at b2.
+// The contractions are dense (layer 2 is 84 % of the predictor's arithmetic), which is what MFMA is for;
+// f16 operands with fp32 accumulation move pred by about 1e-4 of its magnitude at worst (eleven
+// significant bits per operand, exact products).
+//
+// Workgroups are dispatched at a finite rate, and one 126-column tile is only a few microseconds of
+// work, so a workgroup walks a contiguous range of tiles of its instance: the x rows and the state of
+// tile t + 1 are fetched into registers while tile t is computed, and the operand tables are loaded once.
+__global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __restrict__ hist,
+                                                               const float* __restrict__ wts_global, int R, int H,
+                                                               int newest_slot, int nb_cur, int nb_cap, int advance,
+                                                               float* __restrict__ pstate, float* __restrict__ pred) {
+  constexpr int C = 8, IW = 126, XW = 130, YW = 128, LD = 128, XBUF = 2 * 5 * XW + 12;
+  constexpr float kScale = 4096.f, kInvScale = 1.f / 4096.f;
+  extern __shared__ __align__(16) float smem[];
+  half8* s_y1 = reinterpret_cast<half8*>(smem);          // [2][4][YW] x 8 f16 (reads may run 2 entries past a row)
+  float* s_xb = smem + 2 * 4 * YW * 4;                   // 2 buffers of [2][5][XW]
+  float* s_red = s_xb + 2 * XBUF;                        // [2][2][LD]
+
+  const int tiles = (nb_cur + IW - 1) / IW;
+  const int per_wg = (tiles + gridDim.x - 1) / gridDim.x;
+  const int t_begin = blockIdx.x * per_wg;
+  const int t_end = min(tiles, t_begin + per_wg);
+  if (t_begin >= t_end) return;
+
+  const int inst = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int hf = wave >> 1;
+  const int n = lane & 31, hsel = lane >> 5;
+  const float* hist_inst = hist + (size_t)inst * R * nb_cap;
+  float* pstate_inst = pstate + (size_t)inst * nb_cap;
+  float* pred_inst = pred + (size_t)inst * nb_cap;
+
+  // Operand tables and per-lane constants.
+  const half8* tab2 = reinterpret_cast<const half8*>(wts_global + kMfmaTableFloatOffset) + (size_t)hf * 6 * kWave;
+  const half8* tab1 = reinterpret_cast<const half8*>(wts_global + kMfmaTableFloatOffset) + 2 * 6 * kWave + hf * kWave;
+  half8 A2[6];
+#pragma unroll
+  for (int s = 0; s < 6; ++s) A2[s] = tab2[s * kWave + lane];
+  const half8 A1 = tab1[lane];
+  float b1v[4], b2v[4], w3v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    b1v[j] = wts_global[9 * C + 4 * hsel + j];
+    b2v[j] = wts_global[10 * C + 9 * C * C + 4 * hsel + j];
+    w3v[j] = wts_global[10 * C + 9 * C * C + C + 4 * hsel + j];
+  }
+  const float b3 = wts_global[10 * C + 9 * C * C + 2 * C];
+  // layer-1 K slot e of this lane is (x row, kw) = divmod(8 hsel + e, 3); slot 15 is unused
+  int xoff[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int ka = e, kb = 8 + e;
+    const int oa = (ka / 3) * XW + ka % 3, ob = kb < 15 ? (kb / 3) * XW + kb % 3 : 0;
+    xoff[e] = hsel ? ob : oa;
+  }
+  // x staging: wave w fetches staged rows w, w + 4, w + 8 (of 10: five per half), three column chunks each.
+  const float* xsrc[3];
+#pragma unroll
+  for (int i = 0; i < 3; ++i) {
+    const int rr = min(wave + 4 * i, 9);
+    const int r = rr < 5 ? rr - 1 : H - 10 + rr;          // rows -1..3, then H-5..H-1
+    xsrc[i] = hist_inst + (size_t)ring_slot(newest_slot, H, R, r) * nb_cap;
+  }
+  float xpre[9], pst_cur = 0.f, pst_next = 0.f;
+  auto fetch = [&](int tile, float& pst) {
+    const int c0 = tile * IW;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        const int xc = lane + kWave * c, j = c0 - 2 + xc;
+        xpre[i * 3 + c] = (wave + 4 * i < 10 && xc < XW && j >= 0 && j < nb_cur) ? xsrc[i][j] : 0.f;
+      }
+    pst = (tid < IW && c0 + tid < nb_cur) ? pstate_inst[c0 + tid] : 0.f;
+  };
+  auto stash = [&](float* s_x) {
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) {
+        const int rr = wave + 4 * i, xc = lane + kWave * c;
+        if (rr < 10 && xc < XW) s_x[rr * XW + xc] = xpre[i * 3 + c];
+      }
+  };
+  fetch(t_begin, pst_cur);
+  stash(s_xb);
   __syncthreads();
 
-  const int hf = tid / IW, col = tid - hf * IW;
-  float o0[C2], o1[C2], o2[C2];
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    const int c0 = tile * IW;
+    const float* s_x = s_xb + ((tile - t_begin) & 1) * XBUF;
+    const bool more = tile + 1 < t_end;
+    if (more) fetch(tile + 1, pst_next);
+
+    // Layer 1.
+    const float* xs = s_x + hf * 5 * XW;
 #pragma unroll
-  for (int c = 0; c < C2; ++c) { o0[c] = W.b2[c]; o1[c] = o0[c]; o2[c] = o0[c]; }
-#pragma unroll 1
-  for (int ci = 0; ci < C1; ++ci) {
-    const float* yb = s_y1 + ((hf * 4) * C1 + ci) * YW + col;
-    const_f32_ptr wc = W.w2r + ci * 9 * C2;
-    float y[4][3];
+    for (int blk = 0; blk < 2; ++blk) {
+      const int yc = ((wave & 1) * 2 + blk) * 32 + n;    // y1 column 0..127  <->  tile column c0 - 1 + yc
+      half8 Bhi, Blo;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+      for (int e = 0; e < 8; ++e) {
+        float xv = xs[yc + xoff[e]] * kScale;
+        if (e == 7 && hsel) xv = 0.f;
+        const _Float16 hi = (_Float16)xv;
+        Bhi[e] = hi;
+        Blo[e] = (_Float16)(xv - (float)hi);
+      }
+      float16v acc;
 #pragma unroll
-      for (int kw = 0; kw < 3; ++kw) y[q][kw] = yb[q * C1 * YW + kw];
-    // tap tables (y1 row q feeding tap kh of each output), -1 = outside the window
-    if (hf == 0) {
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, Bhi, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, Blo, acc, 0, 0, 0);
+      const int j = c0 - 1 + yc;
+      const float hi_clamp = (j >= 0 && j < nb_cur) ? INFINITY : 0.f;   // med3(a, 0, inf) = relu(a); med3(a, 0, 0) = 0
 #pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
+      for (int q = 0; q < 4; ++q) {
+        half4 h;
 #pragma unroll
-        for (int c = 0; c < C2; ++c) {
-          o0[c] = fmaf(wc[(0 * 3 + kw) * C2 + c], y[0][kw], o0[c]);
-          o2[c] = fmaf(wc[(0 * 3 + kw) * C2 + c], y[1][kw], o2[c]);
-        }
-#pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-        for (int c = 0; c < C2; ++c) {
-          o0[c] = fmaf(wc[(1 * 3 + kw) * C2 + c], y[2][kw], o0[c]);
-          o1[c] = fmaf(wc[(1 * 3 + kw) * C2 + c], y[1][kw], o1[c]);
-          o2[c] = fmaf(wc[(1 * 3 + kw) * C2 + c], y[2][kw], o2[c]);
-        }
-#pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-        for (int c = 0; c < C2; ++c) {
-          o0[c] = fmaf(wc[(2 * 3 + kw) * C2 + c], y[3][kw], o0[c]);
-          o1[c] = fmaf(wc[(2 * 3 + kw) * C2 + c], y[2][kw], o1[c]);
-          o2[c] = fmaf(wc[(2 * 3 + kw) * C2 + c], y[3][kw], o2[c]);
-        }
-    } else {
-#pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-        for (int c = 0; c < C2; ++c) {
-          o0[c] = fmaf(wc[(0 * 3 + kw) * C2 + c], y[0][kw], o0[c]);
-          o1[c] = fmaf(wc[(0 * 3 + kw) * C2 + c], y[1][kw], o1[c]);
-          o2[c] = fmaf(wc[(0 * 3 + kw) * C2 + c], y[2][kw], o2[c]);
-        }
-#pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-        for (int c = 0; c < C2; ++c) {
-          o0[c] = fmaf(wc[(1 * 3 + kw) * C2 + c], y[1][kw], o0[c]);
-          o1[c] = fmaf(wc[(1 * 3 + kw) * C2 + c], y[2][kw], o1[c]);
-          o2[c] = fmaf(wc[(1 * 3 + kw) * C2 + c], y[3][kw], o2[c]);
-        }
-#pragma unroll
-      for (int kw = 0; kw < 3; ++kw)
-#pragma unroll
-        for (int c = 0; c < C2; ++c) {
-          o0[c] = fmaf(wc[(2 * 3 + kw) * C2 + c], y[2][kw], o0[c]);
-          o1[c] = fmaf(wc[(2 * 3 + kw) * C2 + c], y[3][kw], o1[c]);
-        }
+        for (int c = 0; c < 4; ++c)
+          h[c] = (_Float16)__builtin_amdgcn_fmed3f(fmaf(acc[4 * q + c], kInvScale, b1v[c]), 0.f, hi_clamp);
+        reinterpret_cast<half4*>(s_y1 + (hf * 4 + q) * YW + yc)[hsel] = h;
+      }
     }
-  }
-  float moving = 0.f, border = 0.f;         // head-weighted: the row leaving/entering, the two border rows
+    __syncthreads();
+
+    // Layer 2 and the head.
+    const half8* yh = s_y1 + (size_t)hf * 4 * YW;
 #pragma unroll
-  for (int c = 0; c < C2; ++c) {
-    moving = fmaf(W.w3[c], fmaxf(o0[c], 0.f), moving);
-    border = fmaf(W.w3[c], fmaxf(o1[c], 0.f), border);
-  }
+    for (int blk = 0; blk < 2; ++blk) {
+      const int cb = ((wave & 1) * 2 + blk) * 32;
+      float16v acc;
 #pragma unroll
-  for (int c = 0; c < C2; ++c) border = fmaf(W.w3[c], fmaxf(o2[c], 0.f), border);
-  s_red[(hf * 2 + 0) * IW + col] = moving;
-  s_red[(hf * 2 + 1) * IW + col] = border;
-  __syncthreads();
-  if (tid < IW && c0 + tid < nb_cur) {
-    const size_t o = (size_t)inst * nb_cap + c0 + tid;
-    float st = pstate[o];
-    if (advance) {
-      st = (st - s_red[0 * IW + tid]) + s_red[2 * IW + tid];
-      pstate[o] = st;
+      for (int v = 0; v < 16; ++v) acc[v] = (v < 12) ? b2v[v & 3] : 0.f;
+#pragma unroll
+      for (int s = 0; s < 6; ++s) {
+        const int cc = 2 * s + hsel;                     // K chunk = one (q, kw) pair, 8 channels
+        const int q = cc / 3, kw = cc - 3 * q;
+        const half8 B = yh[q * YW + cb + n + kw];
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(A2[s], B, acc, 0, 0, 0);
+      }
+      float p[3];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        float t = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) t = fmaf(w3v[jj], fmaxf(acc[4 * k + jj], 0.f), t);
+        p[k] = t + __shfl_xor(t, 32, kWave);
+      }
+      if (hsel == 0) {
+        s_red[(hf * 2 + 0) * LD + cb + n] = p[0];
+        s_red[(hf * 2 + 1) * LD + cb + n] = p[1] + p[2];
+      }
     }
-    pred[o] = W.b3[0] + (st + (s_red[1 * IW + tid] + s_red[3 * IW + tid])) / (float)H;
+    __syncthreads();
+    if (tid < IW && c0 + tid < nb_cur) {
+      float st = pst_cur;
+      if (advance) {
+        st = (st - s_red[0 * LD + tid]) + s_red[2 * LD + tid];
+        pstate_inst[c0 + tid] = st;
+      }
+      pred_inst[c0 + tid] = b3 + (st + (s_red[1 * LD + tid] + s_red[3 * LD + tid])) / (float)H;
+    }
+    if (more) stash(s_xb + (((tile - t_begin) & 1) ^ 1) * XBUF);
+    pst_cur = pst_next;
+    __syncthreads();
   }
 }
 
@@ -324,11 +501,19 @@ hipError_t run_full(const Shape& s, const float* dweights, const float* hist, in
 template <int C1, int C2>
 hipError_t run_inc(const Shape& s, const float* dweights, const float* hist, int newest_slot, int nb_cur,
                    int advance, float* pstate, float* pred, hipStream_t st) {
+  if (C1 == 8 && C2 == 8 && s.predictor_mfma) {
+    const size_t lds = sizeof(float) * (2 * 4 * 128 * 4 + 2 * (2 * 5 * 130 + 12) + 4 * 128);
+    const int tiles = (nb_cur + 125) / 126;
+    int chunks = (2048 + s.n_inst - 1) / s.n_inst;       // about eight workgroups per CU when instances are few
+    if (chunks > tiles) chunks = tiles;
+    predict_inc_mfma_kernel<<<dim3(chunks, s.n_inst), 256, lds, st>>>(
+        hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, advance, pstate, pred);
+    return hipGetLastError();
+  }
   constexpr int IW = C1 <= 8 ? 128 : 64;
-  const size_t lds = sizeof(float) * (2 * 5 * (IW + 4) + 2 * 4 * (size_t)C1 * (IW + 2) + 4 * IW);
-  const dim3 grid((nb_cur + IW - 1) / IW, s.n_inst);
-  predict_inc_kernel<C1, C2, IW><<<grid, 2 * IW, lds, st>>>(hist, dweights, s.R, s.H, newest_slot, nb_cur,
-                                                           s.nb_cap, advance, pstate, pred);
+  const size_t lds = sizeof(float) * (2 * 4 * (size_t)C1 * (IW + 2) + 2 * 5 * (IW + 4) + 4 * IW);
+  predict_inc_kernel<C1, C2, IW><<<dim3((nb_cur + IW - 1) / IW, s.n_inst), 2 * IW, lds, st>>>(
+      hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, advance, pstate, pred);
   return hipGetLastError();
 }
 

@@ -11,7 +11,7 @@ from .binding import AP_PRED_ADVANCE, AP_PRED_HOLD, AP_PRED_REBASE, Context
 
 
 class DecodeRun:
-    def __init__(self, w, device="cuda:0", incremental=True, rebase_every=512):
+    def __init__(self, w, device="cuda:0", incremental=True, rebase_every=512, flags=0):
         """incremental: carry the predictor's interior state across steps (ap_predict_incremental)
         and re-evaluate the full tile every `rebase_every` pushes; False evaluates the full tile
         on every step."""
@@ -23,7 +23,7 @@ class DecodeRun:
         self.dev = torch.device(device)
         self.ctx = Context(n_inst=w.n_inst, g=w.g, head_dim=w.head_dim, block=w.block, hist_len=w.hist_len,
                            t_cap=w.t_cap, k_blocks=w.k_blocks, n_sink=w.n_sink, n_local=w.n_local,
-                           c1=w.c1, c2=w.c2, kv_dtype=w.kv_dtype)
+                           c1=w.c1, c2=w.c2, kv_dtype=w.kv_dtype, flags=flags)
         R, nbc = self.ctx.hist_slots(), self.ctx.nb_cap()
         self.R, self.nb_cap = R, nbc
         f32, i32 = torch.float32, torch.int32
