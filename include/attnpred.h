@@ -162,6 +162,15 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
             const void* V, int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred,
             float* pstate, int32_t pred_mode, void* ws, void* stream);
 
+/* Measurement aids (no part of Algorithm 1): a streaming read of `bytes` bytes (multiple of 16) of
+ * device memory with 16-byte loads per lane, and a plain copy.  They give the read bandwidth the
+ * machine actually reaches, quoted beside the published peak, and a kernel of known traffic against
+ * which hardware byte counters are scaled.
+ *   sink  device, at least 16 * n_workgroups bytes (read: one checksum word per workgroup is xor-ed in)
+ *   dst   device, `bytes` bytes */
+int ap_stream_read(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream);
+int ap_stream_copy(const void* src, size_t bytes, void* dst, int32_t n_workgroups, void* stream);
+
 const char* ap_strerror(int code);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ AP_FLAG_PREDICTOR_FP32 = 1
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights",
     "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
-    "ap_strerror",
+    "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
 
 
@@ -67,6 +67,8 @@ def load_library() -> C.CDLL:
     lib.ap_calibrate.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.ap_update_history.argtypes = [vp, vp, i64, vp, vp]
     lib.ap_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.ap_stream_read.argtypes = [vp, sz, vp, i32, vp]
+    lib.ap_stream_copy.argtypes = [vp, sz, vp, i32, vp]
     lib.ap_strerror.argtypes = [C.c_int]
     lib.ap_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -89,6 +91,16 @@ def _ptr(t: torch.Tensor) -> int:
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor, n_workgroups: int) -> None:
+    _check(load_library().ap_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), n_workgroups,
+                                         _stream()))
+
+
+def stream_copy(src: torch.Tensor, dst: torch.Tensor, n_workgroups: int) -> None:
+    _check(load_library().ap_stream_copy(_ptr(src), src.numel() * src.element_size(), _ptr(dst), n_workgroups,
+                                         _stream()))
 
 
 class Context:

@@ -74,6 +74,8 @@ hipError_t launch_sparse_decode(const Shape& s, const void* q, const void* K, co
                                 size_t row_stride, float* ws, hipStream_t st);
 hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row,
                             float* ws, hipStream_t st);
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int n_wg, hipStream_t st);
+hipError_t launch_stream_copy(const void* src, size_t bytes, void* dst, int n_wg, hipStream_t st);
 hipError_t launch_push_row(const Shape& s, float* hist, int slot, const float* row, hipStream_t st);
 
 }  // namespace ap

@@ -296,6 +296,20 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
   return AP_OK;
 }
 
+int ap_stream_read(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream) {
+  AP_REQUIRE_PTR(src); AP_REQUIRE_PTR(sink);
+  if (bytes < 16 || n_workgroups < 1 || n_workgroups > 65535) return AP_ERR_ARG;
+  return ap::launch_stream_read(src, bytes, sink, n_workgroups, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_stream_copy(const void* src, size_t bytes, void* dst, int32_t n_workgroups, void* stream) {
+  AP_REQUIRE_PTR(src); AP_REQUIRE_PTR(dst);
+  if (bytes < 16 || n_workgroups < 1 || n_workgroups > 65535) return AP_ERR_ARG;
+  return ap::launch_stream_copy(src, bytes, dst, n_workgroups, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? AP_OK : AP_ERR_HIP;
+}
+
 const char* ap_strerror(int code) {
   switch (code) {
     case AP_OK: return "ok";

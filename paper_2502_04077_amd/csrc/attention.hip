@@ -12,12 +12,16 @@
 // Memory access: a K or V row is d * sizeof(T) bytes (256 B for bf16, d = 128).  LPT = row bytes / 16
 // adjacent lanes read one row with one 16-byte load each, so every load instruction of a wave covers
 // 64 / LPT whole rows = 1 KiB of contiguous memory inside a block.
+#include <type_traits>
+
 #include "ap_internal.h"
 
 namespace ap {
 namespace {
 
 struct bf16_t { uint16_t bits; };
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
 
 template <typename T> struct KvT;
 template <> struct KvT<float> { static constexpr int E = 4; };
@@ -68,58 +72,111 @@ template <typename T, int D, int G> struct Geom {
 };
 
 // Phase 1.  `block_of(jb)` gives the block index of list position jb.  s_p is [G][ld].
+//
+// bf16: the g x d by d x 16-token contraction runs on v_mfma_f32_16x16x32_bf16 (A = 16 K rows, B = q^T
+// padded to 16 columns, fp32 accumulate); with VALU dot products plus cross-lane sums the kernel spends
+// two thirds of its issue slots on arithmetic and cannot keep HBM busy.  Lane l supplies token l % 16,
+// dims 32 s + 8 (l / 16) .. + 7 of K-step s, straight from global memory: one load instruction covers
+// 16 rows x 64 contiguous bytes, and the next step takes the other half of the same 128-byte lines.
+// D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so lanes with head < G hold the logits.
+// fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
 template <typename T, int D, int G, class BlockOf>
 __device__ inline void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
                                  int t_cur, int ntok, BlockOf block_of, float* s_p, int ld) {
-  using Ge = Geom<T, D, G>;
-  constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
-  const int dpart = lane % LPT;
-  const int tslot = lane / LPT;
-
-  float qr[G][E];
   const float scale = rsqrtf((float)D);
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    static_assert(E * sizeof(T) == 16, "one 16-byte load per lane");
-    uint4 w = *reinterpret_cast<const uint4*>(q_inst + (size_t)h * D + dpart * E);
-    float f[E];
-    unpack16(w, f, T{});
-#pragma unroll
-    for (int e = 0; e < E; ++e) qr[h][e] = f[e] * scale;
-  }
-
   const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
-  for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
-    uint4 kw[NL];
-    int gtok[NL];
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    constexpr int KS = D / 32;
+    const int row = lane & 15, g = lane >> 4;
+    bf16x8 qb[KS];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int tau = grp * kGroupTokens + i * TPI + tslot;
-      kw[i] = make_uint4(0, 0, 0, 0);
-      gtok[i] = -1;
+    for (int s = 0; s < KS; ++s) {
+      uint4 w = make_uint4(0, 0, 0, 0);
+      if (row < G) w = *reinterpret_cast<const uint4*>(q_inst + (size_t)row * D + s * 32 + g * 8);
+      qb[s] = __builtin_bit_cast(bf16x8, w);
+    }
+    auto load_group = [&](int grp, uint4 (&kw)[KS]) {
+      const int tau = grp * kGroupTokens + row;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
       if (tau < ntok) {
-        const int blk = block_of(tau >> log2b);
-        gtok[i] = blk * b + (tau & (b - 1));
-        kw[i] = *reinterpret_cast<const uint4*>(K_inst + (size_t)gtok[i] * D + dpart * E);
+        const int gtok = block_of(tau >> log2b) * b + (tau & (b - 1));
+        const T* src = K_inst + (size_t)gtok * D + g * 8;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kw[s] = *reinterpret_cast<const uint4*>(src + s * 32);
+      }
+    };
+    uint4 cur[KS], nxt[KS];
+    if (wave < ngroups) load_group(wave, cur);
+    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      const bool more = grp + kAttnWaves < ngroups;
+      if (more) load_group(grp + kAttnWaves, nxt);
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[s]), qb[s], acc, 0, 0, 0);
+      const int tau0 = grp * kGroupTokens + 4 * g;       // four tokens of one block (b is a multiple of 8)
+      if (row < G && tau0 < ntok) {
+        const int gtok0 = block_of(tau0 >> log2b) * b + (tau0 & (b - 1));
+        float4 o;
+        o.x = gtok0 + 0 < t_cur ? acc[0] * scale : -INFINITY;
+        o.y = gtok0 + 1 < t_cur ? acc[1] * scale : -INFINITY;
+        o.z = gtok0 + 2 < t_cur ? acc[2] * scale : -INFINITY;
+        o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
+        *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
+      }
+      if (more) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) cur[s] = nxt[s];
       }
     }
+  } else {
+    using Ge = Geom<T, D, G>;
+    constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
+    const int dpart = lane % LPT;
+    const int tslot = lane / LPT;
+    float qr[G][E];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int tau = grp * kGroupTokens + i * TPI + tslot;
-      float kf[E];
-      unpack16(kw[i], kf, T{});
-      float mine = 0.f;
+    for (int h = 0; h < G; ++h) {
+      static_assert(E * sizeof(T) == 16, "one 16-byte load per lane");
+      uint4 w = *reinterpret_cast<const uint4*>(q_inst + (size_t)h * D + dpart * E);
+      float f[E];
+      unpack16(w, f, T{});
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        float s = 0.f;
+      for (int e = 0; e < E; ++e) qr[h][e] = f[e] * scale;
+    }
+    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      uint4 kw[NL];
+      int gtok[NL];
 #pragma unroll
-        for (int e = 0; e < E; ++e) s = fmaf(qr[h][e], kf[e], s);
-        s = lane_group_sum<LPT>(s);
-        if (dpart == h) mine = s;
+      for (int i = 0; i < NL; ++i) {
+        const int tau = grp * kGroupTokens + i * TPI + tslot;
+        kw[i] = make_uint4(0, 0, 0, 0);
+        gtok[i] = -1;
+        if (tau < ntok) {
+          const int blk = block_of(tau >> log2b);
+          gtok[i] = blk * b + (tau & (b - 1));
+          kw[i] = *reinterpret_cast<const uint4*>(K_inst + (size_t)gtok[i] * D + dpart * E);
+        }
       }
-      if (dpart < G && tau < ntok) s_p[dpart * ld + tau] = (gtok[i] < t_cur) ? mine : -INFINITY;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int tau = grp * kGroupTokens + i * TPI + tslot;
+        float kf[E];
+        unpack16(kw[i], kf, T{});
+        float mine = 0.f;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          float sdot = 0.f;
+#pragma unroll
+          for (int e = 0; e < E; ++e) sdot = fmaf(qr[h][e], kf[e], sdot);
+          sdot = lane_group_sum<LPT>(sdot);
+          if (dpart == h) mine = sdot;
+        }
+        if (dpart < G && tau < ntok) s_p[dpart * ld + tau] = (gtok[i] < t_cur) ? mine : -INFINITY;
+      }
     }
   }
 }

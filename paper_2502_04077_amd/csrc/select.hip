@@ -19,6 +19,24 @@ __device__ inline uint32_t score_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);    // larger score <=> larger key
 }
 
+// Adds one to hist[bin] for every lane with `active`.  Predicted scores of neighbouring blocks are close,
+// so most lanes of a wave share a bin and per-lane LDS atomics would serialise on it: the two most common
+// leading bins are counted with a ballot and added once per wave, the rest fall back to single adds.
+__device__ inline void hist_add(uint32_t* hist, uint32_t bin, bool active) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    const unsigned long long live = __ballot(active);
+    if (live == 0) return;
+    const int leader = __ffsll((long long)live) - 1;
+    const uint32_t b0 = (uint32_t)__shfl((int)bin, leader, kWave);
+    const unsigned long long same = __ballot(active && bin == b0);
+    if (lane == leader) atomicAdd(&hist[b0], (uint32_t)__popcll(same));
+    if (bin == b0) active = false;
+  }
+  if (active) atomicAdd(&hist[bin], 1u);
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* __restrict__ pred, int nb_cap,
                                                                   int nb_cur, int k, int n_sink, int n_local,
                                                                   int32_t* __restrict__ idx,
@@ -47,10 +65,15 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
     for (int shift = 24; shift >= 0; shift -= 8) {
       s_hist[tid] = 0;
       __syncthreads();
-      for (int j = lo + tid; j < hi; j += kSelThreads) {
-        const uint32_t key = score_key(p[j]);
-        const bool match = (shift == 24) || ((key >> (shift + 8)) == prefix);
-        if (match) atomicAdd(&s_hist[(key >> shift) & 255u], 1u);
+      for (int jb = lo; jb < hi; jb += kSelThreads) {        // uniform trip count: ballots need every lane
+        const int j = jb + tid;
+        uint32_t key = 0;
+        bool match = false;
+        if (j < hi) {
+          key = score_key(p[j]);
+          match = (shift == 24) || ((key >> (shift + 8)) == prefix);
+        }
+        hist_add(s_hist, (key >> shift) & 255u, match);
       }
       __syncthreads();
       // Suffix sums over bins: thread r handles bin 255 - r, inclusive scan in that order.
