@@ -60,17 +60,18 @@ constexpr int kMfmaTableHalfs = 2 * 6 * 64 * 8 + 2 * 64 * 8;
 
 // Launchers.  Each returns hipSuccess or the launch error.
 // Full-tile predictor over columns [col_begin, nb_cur); also writes the interior state if pstate != null.
-hipError_t launch_predict(const Shape& s, const float* dweights, const float* hist, int newest_slot,
-                          int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st);
+// Launchers that take (inst0, ninst) work on instances [inst0, inst0 + ninst) of the same buffers.
+hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                          int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st);
 // Incremental predictor over all columns; advance != 0 moves the state forward by one pushed row first.
-hipError_t launch_predict_inc(const Shape& s, const float* dweights, const float* hist, int newest_slot,
-                              int nb_cur, int advance, float* pstate, float* pred, hipStream_t st);
-hipError_t launch_select(const Shape& s, const float* pred, int nb_cur, int32_t* idx, int32_t* cnt,
-                         hipStream_t st);
+hipError_t launch_predict_inc(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                              int newest_slot, int nb_cur, int advance, float* pstate, float* pred, hipStream_t st);
+hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred, int nb_cur, int32_t* idx,
+                         int32_t* cnt, hipStream_t st);
 // row_stride: floats between consecutive instances' rows (nb_cap for a plain row buffer,
 // R * nb_cap when writing straight into a ring slot).
-hipError_t launch_sparse_decode(const Shape& s, const void* q, const void* K, const void* V, int t_cur,
-                                const int32_t* idx, const int32_t* cnt, float* out, float* row,
+hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void* q, const void* K, const void* V,
+                                int t_cur, const int32_t* idx, const int32_t* cnt, float* out, float* row,
                                 size_t row_stride, float* ws, hipStream_t st);
 hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row,
                             float* ws, hipStream_t st);

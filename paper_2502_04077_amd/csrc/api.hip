@@ -192,17 +192,18 @@ static int run_predictor(const ap_ctx* ctx, const float* hist, int64_t n_pushed,
   const Shape& s = ctx->s;
   const int newest = newest_slot_of(s, n_pushed);
   if (pstate == nullptr || mode == AP_PRED_REBASE || s.H < 6) {
-    return ap::launch_predict(s, ctx->dweights, hist, newest, nb_cur, 0, pstate, pred, st) == hipSuccess ? AP_OK
-                                                                                                          : AP_ERR_HIP;
+    return ap::launch_predict(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, 0, pstate, pred, st) == hipSuccess
+               ? AP_OK : AP_ERR_HIP;
   }
-  if (ap::launch_predict_inc(s, ctx->dweights, hist, newest, nb_cur, mode == AP_PRED_ADVANCE, pstate, pred, st) !=
-      hipSuccess)
+  if (ap::launch_predict_inc(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, mode == AP_PRED_ADVANCE, pstate,
+                             pred, st) != hipSuccess)
     return AP_ERR_HIP;
   if (nb_cur > nb_prev) {
     // The tile grew: column nb_prev - 1 gained a right neighbour inside the tile and the new columns
     // have no state yet; evaluate those columns in full.
     const int col_begin = nb_prev > 1 ? nb_prev - 1 : 0;
-    if (ap::launch_predict(s, ctx->dweights, hist, newest, nb_cur, col_begin, pstate, pred, st) != hipSuccess)
+    if (ap::launch_predict(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, col_begin, pstate, pred, st) !=
+        hipSuccess)
       return AP_ERR_HIP;
   }
   return AP_OK;
@@ -237,7 +238,7 @@ int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx,
   AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt); AP_REQUIRE_PTR(ws);
   const Shape& s = ctx->s;
   if (nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
-  hipError_t e = ap::launch_select(s, pred, nb_cur, idx, cnt, static_cast<hipStream_t>(stream));
+  hipError_t e = ap::launch_select(s, 0, s.n_inst, pred, nb_cur, idx, cnt, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
@@ -248,7 +249,7 @@ int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, i
   AP_REQUIRE_PTR(out); AP_REQUIRE_PTR(row); AP_REQUIRE_PTR(ws);
   const Shape& s = ctx->s;
   if (t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
-  hipError_t e = ap::launch_sparse_decode(s, q, K, V, t_cur, idx, cnt, out, row, (size_t)s.nb_cap,
+  hipError_t e = ap::launch_sparse_decode(s, 0, s.n_inst, q, K, V, t_cur, idx, cnt, out, row, (size_t)s.nb_cap,
                                           static_cast<float*>(ws), static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
@@ -287,10 +288,10 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
   hipStream_t st = static_cast<hipStream_t>(stream);
   int rc = run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, pred_mode, pstate, pred, st);
   if (rc != AP_OK) return rc;
-  if (ap::launch_select(s, pred, nb_cur, idx, cnt, st) != hipSuccess) return AP_ERR_HIP;
+  if (ap::launch_select(s, 0, s.n_inst, pred, nb_cur, idx, cnt, st) != hipSuccess) return AP_ERR_HIP;
   const int slot = (int)(n_pushed % s.R);
   float* slot_row = hist + (size_t)slot * s.nb_cap;
-  if (ap::launch_sparse_decode(s, q, K, V, t_cur, idx, cnt, out, slot_row, (size_t)s.R * s.nb_cap,
+  if (ap::launch_sparse_decode(s, 0, s.n_inst, q, K, V, t_cur, idx, cnt, out, slot_row, (size_t)s.R * s.nb_cap,
                                static_cast<float*>(ws), st) != hipSuccess)
     return AP_ERR_HIP;
   return AP_OK;

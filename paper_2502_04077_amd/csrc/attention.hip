@@ -230,7 +230,7 @@ struct SparseArgs {
   const int32_t* idx; const int32_t* cnt;
   float* out; float* row; size_t row_stride;
   float* part_ml; float* part_acc; float* part_bmp;
-  int t_cap, nb_cap, k, b, log2b, t_cur, nb_cur, n_split, blk_per_split;
+  int t_cap, nb_cap, k, b, log2b, t_cur, nb_cur, n_split, blk_per_split, inst0;
 };
 
 template <typename T, int D, int G>
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_decode_kernel(SparseArgs 
   using Ge = Geom<T, D, G>;
   constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
   extern __shared__ __align__(16) float smem[];
-  const int inst = blockIdx.y, split = blockIdx.x;
+  const int inst = a.inst0 + blockIdx.y, split = blockIdx.x;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int dpart = lane % LPT, tslot = lane / LPT;
 
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_decode_kernel(SparseArgs 
 template <int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs a) {
   extern __shared__ __align__(16) float smem[];
-  const int inst = blockIdx.x;
+  const int inst = a.inst0 + blockIdx.x;
   const int cnt = min(max(a.cnt[inst], 0), a.k);
   float* s_scale = smem;                               // [n_split][G]  exp(m_s - M) / L
   float* s_rowval = s_scale + a.n_split * G;           // [k]
@@ -479,15 +479,15 @@ __global__ __launch_bounds__(kAttnThreads) void calibrate_finish_kernel(CalibArg
 int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 
 template <typename T, int D, int G>
-hipError_t run_sparse(const Shape& s, SparseArgs a, hipStream_t st) {
+hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
   const size_t lds = sizeof(float) * ((size_t)G * nblk_cap * a.b + kAttnWaves * G * D + G * nblk_cap + nblk_cap + 2 * G) +
                      sizeof(int) * nblk_cap;
-  sparse_decode_kernel<T, D, G><<<dim3(a.n_split, s.n_inst), kAttnThreads, lds, st>>>(a);
+  sparse_decode_kernel<T, D, G><<<dim3(a.n_split, ninst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.n_split == 1) return e;
   const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G + a.k) + sizeof(int) * a.k;
-  sparse_combine_kernel<D, G><<<dim3(s.n_inst), kAttnThreads, lds2, st>>>(a);
+  sparse_combine_kernel<D, G><<<dim3(ninst), kAttnThreads, lds2, st>>>(a);
   return hipGetLastError();
 }
 
@@ -521,8 +521,8 @@ hipError_t run_calib(const Shape& s, CalibArgs a, hipStream_t st) {
 
 }  // namespace
 
-hipError_t launch_sparse_decode(const Shape& s, const void* q, const void* K, const void* V, int t_cur,
-                                const int32_t* idx, const int32_t* cnt, float* out, float* row,
+hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void* q, const void* K, const void* V,
+                                int t_cur, const int32_t* idx, const int32_t* cnt, float* out, float* row,
                                 size_t row_stride, float* ws, hipStream_t st) {
   const WsLayout wl = ws_layout(s);
   SparseArgs a;
@@ -532,7 +532,8 @@ hipError_t launch_sparse_decode(const Shape& s, const void* q, const void* K, co
   a.nb_cur = (t_cur + s.b - 1) / s.b;
   a.n_split = s.n_split;
   a.blk_per_split = (s.k + s.n_split - 1) / s.n_split;
-  AP_DISPATCH(run_sparse, s, a, st)
+  a.inst0 = inst0;
+  AP_DISPATCH(run_sparse, s, ninst, a, st)
 }
 
 hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row, float* ws,

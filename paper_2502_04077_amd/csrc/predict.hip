@@ -80,7 +80,8 @@ template <int C1, int C2>
 __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float* __restrict__ hist,
                                                                     const float* __restrict__ wts_global, int R,
                                                                     int H, int newest_slot, int nb_cur, int nb_cap,
-                                                                    int col_begin, float* __restrict__ pstate,
+                                                                    int inst0, int col_begin,
+                                                                    float* __restrict__ pstate,
                                                                     float* __restrict__ pred) {
   extern __shared__ __align__(16) float smem[];
   float* s_x = smem;                        // [kXR][kXW]
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
   float* s_z = s_y1;                        // [4][2][kTW] after the last strip
   const Weights<C1, C2> W(wts_global);
 
-  const int inst = blockIdx.y;
+  const int inst = inst0 + blockIdx.y;
   const int c0 = col_begin + blockIdx.x * kTW;   // first output column of this tile
   const int tid = threadIdx.x;
   const int col = tid & (kTW - 1);
@@ -251,8 +252,9 @@ __device__ inline void finish_column(const float* s_red, int tid, size_t o, int 
 template <int C1, int C2, int IW>
 __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __restrict__ hist,
                                                              const float* __restrict__ wts_global, int R, int H,
-                                                             int newest_slot, int nb_cur, int nb_cap, int advance,
-                                                             float* __restrict__ pstate, float* __restrict__ pred) {
+                                                             int newest_slot, int nb_cur, int nb_cap, int inst0,
+                                                             int advance, float* __restrict__ pstate,
+                                                             float* __restrict__ pred) {
   constexpr int XW = IW + 4, YW = IW + 2, NT = 2 * IW;
   extern __shared__ __align__(16) float smem[];
   float* s_y1 = smem;                       // [2][4][C1][YW]
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
   float* s_red = s_x + 2 * 5 * XW;          // [2][2][IW]
   const Weights<C1, C2> W(wts_global);
 
-  const int inst = blockIdx.y;
+  const int inst = inst0 + blockIdx.y;
   const int c0 = blockIdx.x * IW;
   const int tid = threadIdx.x;
   stage_x_rows<XW, NT / kWave>(s_x, hist + (size_t)inst * R * nb_cap, newest_slot, H, R, nb_cap, nb_cur, c0);
@@ -327,8 +329,9 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
 // tile t + 1 are fetched into registers while tile t is computed, and the operand tables are loaded once.
 __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __restrict__ hist,
                                                                const float* __restrict__ wts_global, int R, int H,
-                                                               int newest_slot, int nb_cur, int nb_cap, int advance,
-                                                               float* __restrict__ pstate, float* __restrict__ pred) {
+                                                               int newest_slot, int nb_cur, int nb_cap, int inst0,
+                                                               int advance, float* __restrict__ pstate,
+                                                               float* __restrict__ pred) {
   constexpr int C = 8, IW = 126, XW = 130, YW = 128, LD = 128, XBUF = 2 * 5 * XW + 12;
   constexpr float kScale = 4096.f, kInvScale = 1.f / 4096.f;
   extern __shared__ __align__(16) float smem[];
@@ -342,7 +345,7 @@ __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __re
   const int t_end = min(tiles, t_begin + per_wg);
   if (t_begin >= t_end) return;
 
-  const int inst = blockIdx.y;
+  const int inst = inst0 + blockIdx.y;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int hf = wave >> 1;
   const int n = lane & 31, hsel = lane >> 5;
@@ -488,52 +491,56 @@ __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __re
 }
 
 template <int C1, int C2>
-hipError_t run_full(const Shape& s, const float* dweights, const float* hist, int newest_slot, int nb_cur,
-                    int col_begin, float* pstate, float* pred, hipStream_t st) {
+hipError_t run_full(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist, int newest_slot,
+                    int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st) {
   static_assert(C1 * kYR * kYW >= 8 * kTW, "s_z aliases s_y1");
   const size_t lds = sizeof(float) * (kXR * kXW + (size_t)C1 * kYR * kYW);
-  const dim3 grid((nb_cur - col_begin + kTW - 1) / kTW, s.n_inst);
+  const dim3 grid((nb_cur - col_begin + kTW - 1) / kTW, ninst);
   predict_full_kernel<C1, C2><<<grid, kPredThreads, lds, st>>>(hist, dweights, s.R, s.H, newest_slot, nb_cur,
-                                                              s.nb_cap, col_begin, pstate, pred);
+                                                              s.nb_cap, inst0, col_begin, pstate, pred);
   return hipGetLastError();
 }
 
 template <int C1, int C2>
-hipError_t run_inc(const Shape& s, const float* dweights, const float* hist, int newest_slot, int nb_cur,
-                   int advance, float* pstate, float* pred, hipStream_t st) {
+hipError_t run_inc(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist, int newest_slot,
+                   int nb_cur, int advance, float* pstate, float* pred, hipStream_t st) {
   if (C1 == 8 && C2 == 8 && s.predictor_mfma) {
     const size_t lds = sizeof(float) * (2 * 4 * 128 * 4 + 2 * (2 * 5 * 130 + 12) + 4 * 128);
     const int tiles = (nb_cur + 125) / 126;
     int chunks = (2048 + s.n_inst - 1) / s.n_inst;       // about eight workgroups per CU when instances are few
     if (chunks > tiles) chunks = tiles;
-    predict_inc_mfma_kernel<<<dim3(chunks, s.n_inst), 256, lds, st>>>(
-        hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, advance, pstate, pred);
+    predict_inc_mfma_kernel<<<dim3(chunks, ninst), 256, lds, st>>>(
+        hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, advance, pstate, pred);
     return hipGetLastError();
   }
   constexpr int IW = C1 <= 8 ? 128 : 64;
   const size_t lds = sizeof(float) * (2 * 4 * (size_t)C1 * (IW + 2) + 2 * 5 * (IW + 4) + 4 * IW);
-  predict_inc_kernel<C1, C2, IW><<<dim3((nb_cur + IW - 1) / IW, s.n_inst), 2 * IW, lds, st>>>(
-      hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, advance, pstate, pred);
+  predict_inc_kernel<C1, C2, IW><<<dim3((nb_cur + IW - 1) / IW, ninst), 2 * IW, lds, st>>>(
+      hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, advance, pstate, pred);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_predict(const Shape& s, const float* dweights, const float* hist, int newest_slot,
-                          int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st) {
-  if (s.c1 == 4 && s.c2 == 4) return run_full<4, 4>(s, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
-  if (s.c1 == 8 && s.c2 == 8) return run_full<8, 8>(s, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
+hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                          int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st) {
+  if (s.c1 == 4 && s.c2 == 4)
+    return run_full<4, 4>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
+  if (s.c1 == 8 && s.c2 == 8)
+    return run_full<8, 8>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
   if (s.c1 == 16 && s.c2 == 32)
-    return run_full<16, 32>(s, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
+    return run_full<16, 32>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_predict_inc(const Shape& s, const float* dweights, const float* hist, int newest_slot,
-                              int nb_cur, int advance, float* pstate, float* pred, hipStream_t st) {
-  if (s.c1 == 4 && s.c2 == 4) return run_inc<4, 4>(s, dweights, hist, newest_slot, nb_cur, advance, pstate, pred, st);
-  if (s.c1 == 8 && s.c2 == 8) return run_inc<8, 8>(s, dweights, hist, newest_slot, nb_cur, advance, pstate, pred, st);
+hipError_t launch_predict_inc(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                              int newest_slot, int nb_cur, int advance, float* pstate, float* pred, hipStream_t st) {
+  if (s.c1 == 4 && s.c2 == 4)
+    return run_inc<4, 4>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, advance, pstate, pred, st);
+  if (s.c1 == 8 && s.c2 == 8)
+    return run_inc<8, 8>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, advance, pstate, pred, st);
   if (s.c1 == 16 && s.c2 == 32)
-    return run_inc<16, 32>(s, dweights, hist, newest_slot, nb_cur, advance, pstate, pred, st);
+    return run_inc<16, 32>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, advance, pstate, pred, st);
   return hipErrorInvalidValue;
 }
 

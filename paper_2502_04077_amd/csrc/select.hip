@@ -39,14 +39,14 @@ __device__ inline void hist_add(uint32_t* hist, uint32_t bin, bool active) {
 
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* __restrict__ pred, int nb_cap,
                                                                   int nb_cur, int k, int n_sink, int n_local,
-                                                                  int32_t* __restrict__ idx,
+                                                                  int inst0, int32_t* __restrict__ idx,
                                                                   int32_t* __restrict__ cnt) {
   __shared__ uint32_t s_hist[256];
   __shared__ uint32_t s_wsum[kSelWaves];
   __shared__ uint32_t s_bin, s_above;
   __shared__ uint32_t s_wgt[kSelWaves], s_weq[kSelWaves];
 
-  const int inst = blockIdx.x;
+  const int inst = inst0 + blockIdx.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const float* p = pred + (size_t)inst * nb_cap;
   int32_t* out = idx + (size_t)inst * k;
@@ -137,10 +137,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
 
 }  // namespace
 
-hipError_t launch_select(const Shape& s, const float* pred, int nb_cur, int32_t* idx, int32_t* cnt,
-                         hipStream_t st) {
-  select_topk_kernel<<<dim3(s.n_inst), kSelThreads, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local,
-                                                             idx, cnt);
+hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred, int nb_cur, int32_t* idx,
+                         int32_t* cnt, hipStream_t st) {
+  select_topk_kernel<<<dim3(ninst), kSelThreads, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local, inst0,
+                                                          idx, cnt);
   return hipGetLastError();
 }
 

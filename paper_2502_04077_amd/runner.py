@@ -43,11 +43,13 @@ class DecodeRun:
     def nb(self, t):
         return (t + self.w.block - 1) // self.w.block
 
-    def logical_history(self) -> torch.Tensor:
-        """The H-row window in logical order (index H-1 = newest) as a new tensor [n_inst][H][nb_cap]."""
+    def logical_history(self, instances=None) -> torch.Tensor:
+        """The H-row window in logical order (index H-1 = newest) as a new tensor
+        [len(instances) or n_inst][H][nb_cap]."""
         H, R = self.w.hist_len, self.R
-        slots = [(self.n_pushed - H + r) % R for r in range(H)]
-        h = self.hist[:, slots, :].clone()
+        slots = torch.tensor([(self.n_pushed - H + r) % R for r in range(H)], device=self.dev)
+        src = self.hist if instances is None else self.hist[torch.as_tensor(list(instances), device=self.dev)]
+        h = src.index_select(1, slots)
         for r in range(H):
             if self.n_pushed - H + r < 0:
                 h[:, r, :] = 0

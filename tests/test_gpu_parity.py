@@ -323,21 +323,25 @@ def test_update_history_ring_is_a_fifo():
 
 
 # --------------------------------------------------------------------------------------------- whole steps
-def lockstep(w, dev, steps, sample, fused_every=2, incremental=True):
-    """Runs decode steps on the GPU; at each step the oracle starts from the GPU's own history."""
+def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks=(0, -1)):
+    """Runs decode steps on the GPU; at each step the oracle starts from the GPU's own history.
+    Only the sampled instances are copied to the host."""
     run = _run(w, dev)
     run.incremental = incremental
     K, V = kv_cache(w, dev)
     wts = orc.PredictorWeights.from_blob(predictor_weights(w), w.c1, w.c2)
     H, b = w.hist_len, w.block
+    sample = list(sample)
+    pos = {i: n for n, i in enumerate(sample)}
     Kc = {i: to_f64(K[i]) for i in sample}
     Vc = {i: to_f64(V[i]) for i in sample}
+    sel = torch.as_tensor(sample, device=dev)
     # history warm-up: the last H prefill steps, dense rows (appendix "Training Details")
     for j in range(H):
         t = w.t0 - H + 1 + j
         q = queries(w, j - H, dev)
         run.warmup_calibrate(q, K, t)
-        if j in (0, H - 1):
+        if j in [c % H for c in warm_checks]:
             torch.cuda.synchronize()
             for i in sample:
                 ref = orc.dense_row(to_f64(q[i]), Kc[i], b, t)
@@ -348,22 +352,24 @@ def lockstep(w, dev, steps, sample, fused_every=2, incremental=True):
         nb = run.nb(t)
         q = queries(w, s, dev)
         calib = w.is_calibration_step(s)
-        before = run.logical_history().cpu().numpy().astype(np.float64)
+        before = run.logical_history(sample).cpu().numpy().astype(np.float64)
         if s % fused_every == 0:
             run.step(q, K, V, t, calibrate=calib)
         else:
             run.step_unfused(q, K, V, t, calibrate=calib)
         torch.cuda.synchronize()
-        after = run.logical_history().cpu().numpy()
-        pred, idx, cnt = run.pred.cpu().numpy(), run.idx.cpu().numpy(), run.cnt.cpu().numpy()
-        out = run.out.cpu().numpy()
+        after = run.logical_history(sample).cpu().numpy()
+        pred, idx, cnt = run.pred[sel].cpu().numpy(), run.idx[sel].cpu().numpy(), run.cnt[sel].cpu().numpy()
+        out = run.out[sel].cpu().numpy()
+        qs = q[sel]
         for i in sample:
-            qi = to_f64(q[i])
-            ref_pred = orc.predict(before[i], nb, wts)
-            assert_close(pred[i, :nb], ref_pred, f"step {s} inst {i} pred")
-            got_idx = idx[i, :cnt[i]]
+            n = pos[i]
+            qi = to_f64(qs[n])
+            ref_pred = orc.predict(before[n], nb, wts)
+            assert_close(pred[n, :nb], ref_pred, f"step {s} inst {i} pred")
+            got_idx = idx[n, :cnt[n]]
             # decision in the kernel's precision: the oracle's selection on the kernel's fp32 scores
-            exp_idx = orc.select_blocks(pred[i, :nb].astype(np.float64), nb, w.k_blocks, w.n_sink, w.n_local)
+            exp_idx = orc.select_blocks(pred[n, :nb].astype(np.float64), nb, w.k_blocks, w.n_sink, w.n_local)
             assert got_idx.tolist() == exp_idx.tolist(), f"step {s} inst {i}: selection differs"
             # against the oracle's float64 scores only near ties may differ
             o_idx = orc.select_blocks(ref_pred, nb, w.k_blocks, w.n_sink, w.n_local)
@@ -375,12 +381,14 @@ def lockstep(w, dev, steps, sample, fused_every=2, incremental=True):
                 assert gap <= TIE_MARGIN * np.abs(ref_pred).max(), f"step {s} inst {i}: swapped blocks are not a near tie"
             ref_out, A = orc.sparse_attention(qi, Kc[i], Vc[i], got_idx, b, t)
             for h in range(w.g):
-                assert_close(out[i, h], ref_out[h], f"step {s} inst {i} head {h} out")
+                assert_close(out[n, h], ref_out[h], f"step {s} inst {i} head {h} out")
             ref_row = np.zeros(run.nb_cap)
             ref_row[:nb] = orc.dense_row(qi, Kc[i], b, t) if calib else orc.pooled_row(A, b)
-            assert_close(after[i, H - 1], ref_row, f"step {s} inst {i} pushed row")
-            assert np.array_equal(after[i, :H - 1], before[i, 1:].astype(np.float32)), "history did not shift"
+            assert_close(after[n, H - 1], ref_row, f"step {s} inst {i} pushed row")
+            assert np.array_equal(after[n, :H - 1], before[n, 1:].astype(np.float32)), "history did not shift"
             stats["checked"] += 1
+    del K, V, run
+    torch.cuda.empty_cache()
     return stats
 
 
@@ -407,8 +415,44 @@ def test_lockstep_small_bf16_block_boundary():
     print("grow lock-step:", st)
 
 
+def test_lockstep_many_instances():
+    """1040 instances, one workgroup per instance in every kernel."""
+    dev = _dev()
+    w = small("many", kv_heads=8, batch=130, g=4, head_dim=128, t0=630, budget_tokens=256, hist_len=16, steps=8,
+              calib_every=4)
+    st = lockstep(w, dev, w.steps, sample=[0, 259, 260, 519, 520, 779, 780, 1039], fused_every=1)
+    print("many-instance lock-step:", st)
+
+
 def test_lockstep_cfg1_sampled_steps():
     dev = _dev()
     w = CONFIGS["cfg1"].with_(steps=6, calib_every=3)
     st = lockstep(w, dev, w.steps, sample=[0, 5])
     print("cfg1 lock-step:", st)
+
+
+# --------------------------------------------------------------------------------------------- full-size configs
+# The configurations of the task at their real sizes, in the launch configuration the bench times
+# (fused ap_step, incremental predictor), checked on a sample of instances the oracle can afford.
+def test_fullsize_cfg2_sampled():
+    dev = _dev()
+    w = CONFIGS["cfg2"].with_(steps=5, calib_every=3)
+    st = lockstep(w, dev, w.steps, sample=[0, 777, 2047], fused_every=1, warm_checks=(-1,))
+    print("cfg2 full-size lock-step:", st)
+    assert st["checked"] == 15
+
+
+def test_fullsize_cfg3_sampled():
+    dev = _dev()
+    w = CONFIGS["cfg3"].with_(steps=4, calib_every=3)
+    st = lockstep(w, dev, w.steps, sample=[0, 127], fused_every=1, warm_checks=(-1,))
+    print("cfg3 full-size lock-step:", st)
+    assert st["checked"] == 8
+
+
+def test_fullsize_cfg4_sampled():
+    dev = _dev()
+    w = CONFIGS["cfg4"].with_(steps=4, calib_every=3)
+    st = lockstep(w, dev, w.steps, sample=[0, 2500, 4095], fused_every=1, warm_checks=(-1,))
+    print("cfg4 full-size lock-step:", st)
+    assert st["checked"] == 12

@@ -115,40 +115,45 @@ def _gen(device, *seed_words: int) -> torch.Generator:
 
 
 # ---------------------------------------------------------------------------------------------
-# Planted structure (cfg4): coordinates of head_dim reserved for each pattern.
-#   dim 0        sink      : key 0 carries a_sink; every query carries +1
-#   dim 1        stripes   : a seeded set of key positions carries a_stripe; queries carry +1 only
-#                            during the first 40 steps of every 200-step season
-#   dims 2..17   rotary    : 8 (cos, sin) pairs; key i carries the angle theta_m * i and the query
-#                            of token t carries amplitude * angle theta_m * (t - delta) summed over a
-#                            few offsets delta, so logits peak at i = t - delta (slash lines drifting
-#                            one token per step) and, with delta = 0, at the newest tokens
-#   dims 18..    noise     : N(0,1) * value_scale
+# Planted structure (cfg4): coordinates of head_dim reserved for each pattern.  Amplitudes are in
+# logit units (queries carry a factor sqrt(head_dim) so that q.k / sqrt(d) gives them directly).
+#   dim 0          sink      key 0 carries 1; every query carries A_SINK                     (re-access)
+#   dim 1          stripes   16 seeded key positions per instance carry 1; queries carry A_STRIPE during the
+#                            first 40 steps of every 200-step season, 0 otherwise              (seasonal)
+#   dims 2..33     local     16 rotary (cos, sin) pairs with geometric wavelengths: key i carries angle
+#                            theta_m * i, the query of the token at position p carries A_LOCAL * angle
+#                            theta_m * p, so the logit is A_LOCAL * sum_m cos(theta_m (p - i)): a peak of
+#                            16 A_LOCAL at the newest tokens that falls off within a few tens of tokens
+#   dims 34..97    slashes   one-hot code of (block index mod 64) on the keys; the query carries A_SLASH on
+#                            the code of (its own block index - delta) mod 64, delta seeded per instance:
+#                            every 64th block lights up and the lit set moves on by one block every 16
+#                            steps                                                            (sequential)
+#   dims 98..127   noise     N(0,1) * value_scale
 # ---------------------------------------------------------------------------------------------
-_ROT0, _NROT = 2, 8
-_A_SINK, _A_STRIPE, _A_ROT = 6.0, 5.0, 0.75
+_LOC0, _NLOC = 2, 16
+_SL0, _SLP = 34, 64
+_NOISE0 = _SL0 + _SLP
+_A_SINK, _A_STRIPE, _A_LOCAL, _A_SLASH = 13.0, 10.5, 0.7, 7.0
 _SEASON, _SEASON_ON = 200, 40
+_N_STRIPES = 16
 
 
-def _rot_thetas(device) -> torch.Tensor:
-    m = torch.arange(_NROT, device=device, dtype=torch.float64)
-    return 2.0 * math.pi / (48.0 * (1.9 ** m))       # wavelengths 48 .. ~4300 tokens
+def _local_thetas(device) -> torch.Tensor:
+    m = torch.arange(_NLOC, device=device, dtype=torch.float64)
+    return 2.0 * math.pi / (32.0 * (1.66 ** m))       # wavelengths 32 .. ~64K tokens
 
 
-def _slash_offsets(w: Workload, inst: torch.Tensor) -> torch.Tensor:
-    """Three seeded relative offsets per instance (tokens behind the query)."""
-    # Small integer hash of the instance id; no generator state needed.
-    base = (inst.to(torch.int64) * 2654435761 + w.seed * 97) % 1000003
-    o1 = 256 + base % 4096
-    o2 = 6000 + (base // 7) % 8192
-    o3 = 15000 + (base // 13) % 12000
-    return torch.stack([o1, o2, o3], dim=-1)
+def _slash_delta(w: Workload, inst: torch.Tensor) -> torch.Tensor:
+    """Seeded per-instance offset (in blocks) of the slash family."""
+    return (inst.to(torch.int64) * 2654435761 + w.seed * 97) % _SLP
 
 
 def _stripe_positions(w: Workload, inst: int) -> torch.Tensor:
+    """One token in each of 16 distinct seeded blocks, away from the sink and local blocks."""
     rng = np.random.default_rng([w.seed, 77, int(inst)])
-    pos = rng.choice(np.arange(128, w.t0 - 128), size=32, replace=False)
-    return torch.from_numpy(np.sort(pos))
+    nb0 = w.t0 // w.block
+    blocks = rng.choice(np.arange(8, nb0 - 8), size=_N_STRIPES, replace=False)
+    return torch.from_numpy(np.sort(blocks * w.block + rng.integers(0, w.block, size=_N_STRIPES)))
 
 
 def kv_cache(w: Workload, device="cpu", chunk_inst: int = 32):
@@ -180,14 +185,16 @@ def kv_cache(w: Workload, device="cpu", chunk_inst: int = 32):
 def _plant_keys(w: Workload, k: torch.Tensor, i0: int) -> None:
     n, t_cap, _ = k.shape
     dev = k.device
-    k[:, :, 0:_ROT0 + 2 * _NROT] = 0.0
+    k[:, :, 0:_NOISE0] = 0.0
     k[:, 0, 0] = 1.0                                          # sink token
     for j in range(n):
-        pos = _stripe_positions(w, i0 + j).to(dev)
-        k[j, pos, 1] = 1.0                                    # vertical stripes
-    ang = torch.arange(t_cap, device=dev, dtype=torch.float64)[:, None] * _rot_thetas(dev)[None, :]
-    k[:, :, _ROT0:_ROT0 + 2 * _NROT:2] = torch.cos(ang).to(torch.float32)[None]
-    k[:, :, _ROT0 + 1:_ROT0 + 2 * _NROT:2] = torch.sin(ang).to(torch.float32)[None]
+        k[j, _stripe_positions(w, i0 + j).to(dev), 1] = 1.0   # vertical stripes
+    pos = torch.arange(t_cap, device=dev)
+    ang = pos.to(torch.float64)[:, None] * _local_thetas(dev)[None, :]
+    k[:, :, _LOC0:_LOC0 + 2 * _NLOC:2] = torch.cos(ang).to(torch.float32)[None]
+    k[:, :, _LOC0 + 1:_LOC0 + 2 * _NLOC:2] = torch.sin(ang).to(torch.float32)[None]
+    code = (pos // w.block) % _SLP
+    k[:, pos, _SL0 + code] = 1.0                              # block-residue code
 
 
 def queries(w: Workload, step: int, device="cpu") -> torch.Tensor:
@@ -199,21 +206,18 @@ def queries(w: Workload, step: int, device="cpu") -> torch.Tensor:
     q = torch.randn((w.n_inst, w.g, w.head_dim), generator=gq, device=device, dtype=torch.float32)
     q *= w.value_scale
     if w.planted:
-        t = w.t0 + step                                       # position of the querying token
+        p = w.t0 + step                                       # position of the querying (newest) token
         dev = q.device
-        # Logits are q.k / sqrt(d); planted amplitudes are given in logit units.
-        s = math.sqrt(w.head_dim)
-        q[:, :, 0:_ROT0 + 2 * _NROT] = 0.0
-        q[:, :, 0] = _A_SINK * s
-        season_on = (step % _SEASON) < _SEASON_ON
-        q[:, :, 1] = (_A_STRIPE * s) if season_on else 0.0
+        sd = math.sqrt(w.head_dim)
+        q[:, :, 0:_NOISE0] = 0.0
+        q[:, :, 0] = _A_SINK * sd
+        q[:, :, 1] = (_A_STRIPE * sd) if (step % _SEASON) < _SEASON_ON else 0.0
+        ang = float(p) * _local_thetas(dev)
+        q[:, :, _LOC0:_LOC0 + 2 * _NLOC:2] = (_A_LOCAL * sd) * torch.cos(ang).to(torch.float32)[None, None, :]
+        q[:, :, _LOC0 + 1:_LOC0 + 2 * _NLOC:2] = (_A_LOCAL * sd) * torch.sin(ang).to(torch.float32)[None, None, :]
         inst = torch.arange(w.n_inst, device=dev)
-        offs = torch.cat([_slash_offsets(w, inst), torch.zeros((w.n_inst, 1), dtype=torch.int64, device=dev)], dim=1)
-        ang = (t - offs).to(torch.float64)[:, :, None] * _rot_thetas(dev)[None, None, :]   # [inst][4][NROT]
-        qc = (_A_ROT * s) * torch.cos(ang).sum(dim=1)
-        qs = (_A_ROT * s) * torch.sin(ang).sum(dim=1)
-        q[:, :, _ROT0:_ROT0 + 2 * _NROT:2] = qc.to(torch.float32)[:, None, :]
-        q[:, :, _ROT0 + 1:_ROT0 + 2 * _NROT:2] = qs.to(torch.float32)[:, None, :]
+        code = (p // w.block - _slash_delta(w, inst)) % _SLP
+        q[inst, :, _SL0 + code] = _A_SLASH * sd
     return q.to(w.torch_dtype())
 
 
