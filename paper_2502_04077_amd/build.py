@@ -17,6 +17,8 @@ def build_library(verbose: bool = False) -> str:
         "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG_DIR, "csrc"),
         # keep the compiler from forming packed-fp32 VALU ops
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        # MFMA accumulators in ordinary VGPRs: no AGPR <-> VGPR copies around every chain
+        "-mllvm", "-amdgpu-mfma-vgpr-form=1",
         *srcs, "-o", LIB_PATH,
     ]
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -385,28 +385,28 @@ __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __re
     xsrc[i] = hist_inst + (size_t)ring_slot(newest_slot, H, R, r) * nb_cap;
   }
   float xpre[9], pst_cur = 0.f, pst_next = 0.f;
+  // Loads are unconditional on clamped addresses (no divergent branches); the raw values stay untouched in
+  // registers until `stash` masks them, so nothing waits on them while the current tile is computed.
   auto fetch = [&](int tile, float& pst) {
     const int c0 = tile * IW;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
 #pragma unroll
-      for (int c = 0; c < 3; ++c) {
-        const int xc = lane + kWave * c, j = c0 - 2 + xc;
-        xpre[i * 3 + c] = (wave + 4 * i < 10 && xc < XW && j >= 0 && j < nb_cur) ? xsrc[i][j] : 0.f;
-      }
-    pst = (tid < IW && c0 + tid < nb_cur) ? pstate_inst[c0 + tid] : 0.f;
+      for (int c = 0; c < 3; ++c) xpre[i * 3 + c] = xsrc[i][min(max(c0 - 2 + lane + kWave * c, 0), nb_cur - 1)];
+    pst = pstate_inst[min(c0 + tid, nb_cur - 1)];
   };
-  auto stash = [&](float* s_x) {
+  auto stash = [&](int tile, float* s_x) {
+    const int c0 = tile * IW;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
 #pragma unroll
       for (int c = 0; c < 3; ++c) {
-        const int rr = wave + 4 * i, xc = lane + kWave * c;
-        if (rr < 10 && xc < XW) s_x[rr * XW + xc] = xpre[i * 3 + c];
+        const int rr = wave + 4 * i, xc = lane + kWave * c, j = c0 - 2 + xc;
+        if (rr < 10 && xc < XW) s_x[rr * XW + xc] = (j >= 0 && j < nb_cur) ? xpre[i * 3 + c] : 0.f;
       }
   };
   fetch(t_begin, pst_cur);
-  stash(s_xb);
+  stash(t_begin, s_xb);
   __syncthreads();
 
   for (int tile = t_begin; tile < t_end; ++tile) {
@@ -484,7 +484,7 @@ __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __re
       }
       pred_inst[c0 + tid] = b3 + (st + (s_red[1 * LD + tid] + s_red[3 * LD + tid])) / (float)H;
     }
-    if (more) stash(s_xb + (((tile - t_begin) & 1) ^ 1) * XBUF);
+    if (more) stash(tile + 1, s_xb + (((tile - t_begin) & 1) ^ 1) * XBUF);
     pst_cur = pst_next;
     __syncthreads();
   }
