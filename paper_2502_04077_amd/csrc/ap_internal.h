@@ -63,6 +63,10 @@ constexpr int kMfmaTableHalfs = 2 * 6 * 64 * 8 + 2 * 64 * 8;
 // Launchers that take (inst0, ninst) work on instances [inst0, inst0 + ninst) of the same buffers.
 hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                           int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st);
+// The same evaluation for a handful of columns [col_begin, nb_cur): one wave per (instance, column).
+hipError_t launch_predict_columns(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                                  int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred,
+                                  hipStream_t st);
 // Incremental predictor over all columns; advance != 0 moves the state forward by one pushed row first.
 hipError_t launch_predict_inc(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                               int newest_slot, int nb_cur, int advance, float* pstate, float* pred, hipStream_t st);

@@ -202,9 +202,11 @@ static int run_predictor(const ap_ctx* ctx, const float* hist, int64_t n_pushed,
     // The tile grew: column nb_prev - 1 gained a right neighbour inside the tile and the new columns
     // have no state yet; evaluate those columns in full.
     const int col_begin = nb_prev > 1 ? nb_prev - 1 : 0;
-    if (ap::launch_predict(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, col_begin, pstate, pred, st) !=
-        hipSuccess)
-      return AP_ERR_HIP;
+    const hipError_t e =
+        nb_cur - col_begin <= 8
+            ? ap::launch_predict_columns(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, col_begin, pstate, pred, st)
+            : ap::launch_predict(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, col_begin, pstate, pred, st);
+    if (e != hipSuccess) return AP_ERR_HIP;
   }
   return AP_OK;
 }

@@ -490,6 +490,83 @@ __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __re
   }
 }
 
+// Full evaluation of a few columns (the ones whose state is void after the tile has grown by a block):
+// one wave per (instance, column), lanes are time rows.  A lane gathers the 5 x 5 x neighbourhood of its
+// pixel from the ring and evaluates y1 on the 3 x 3 pixels around it channel by channel, feeding y2.
+template <int C1, int C2>
+__global__ __launch_bounds__(kWave) void predict_columns_kernel(const float* __restrict__ hist,
+                                                                const float* __restrict__ wts_global, int R, int H,
+                                                                int newest_slot, int nb_cur, int nb_cap, int inst0,
+                                                                int col_begin, float* __restrict__ pstate,
+                                                                float* __restrict__ pred) {
+  const Weights<C1, C2> W(wts_global);
+  const int inst = inst0 + blockIdx.y;
+  const int j = col_begin + blockIdx.x;
+  const int lane = threadIdx.x;
+  const float* hist_inst = hist + (size_t)inst * R * nb_cap;
+  float w_int = 0.f, w_bor = 0.f;
+  for (int r = lane; r < H; r += kWave) {
+    float x[5][5];
+#pragma unroll
+    for (int dr = 0; dr < 5; ++dr) {
+      const int rr = r - 2 + dr;
+      const bool row_ok = rr >= 0 && rr < H;
+      const float* src = hist_inst + (size_t)ring_slot(newest_slot, H, R, row_ok ? rr : 0) * nb_cap;
+#pragma unroll
+      for (int dc = 0; dc < 5; ++dc) {
+        const int jj = j - 2 + dc;
+        const float v = src[min(max(jj, 0), nb_cur - 1)];
+        x[dr][dc] = (row_ok && jj >= 0 && jj < nb_cur) ? v : 0.f;
+      }
+    }
+    float acc[C2];
+#pragma unroll
+    for (int c = 0; c < C2; ++c) acc[c] = W.b2[c];
+#pragma unroll 1
+    for (int ci = 0; ci < C1; ++ci) {
+      const_f32_ptr wc = W.w2r + ci * 9 * C2;
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+          // y1[ci] at (r + kh - 1, j + kw - 1): zero outside the tile
+          const int rr = r + kh - 1, jj = j + kw - 1;
+          float a = W.b1[ci];
+#pragma unroll
+          for (int a_kh = 0; a_kh < 3; ++a_kh)
+#pragma unroll
+            for (int a_kw = 0; a_kw < 3; ++a_kw)
+              a = fmaf(W.w1r[(a_kh * 3 + a_kw) * C1 + ci], x[kh + a_kh][kw + a_kw], a);
+          const float y = (rr >= 0 && rr < H && jj >= 0 && jj < nb_cur) ? fmaxf(a, 0.f) : 0.f;
+#pragma unroll
+          for (int c = 0; c < C2; ++c) acc[c] = fmaf(wc[(kh * 3 + kw) * C2 + c], y, acc[c]);
+        }
+    }
+    float hsum = 0.f;
+#pragma unroll
+    for (int c = 0; c < C2; ++c) hsum = fmaf(W.w3[c], fmaxf(acc[c], 0.f), hsum);
+    if (r >= 2 && r <= H - 3) w_int += hsum; else w_bor += hsum;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    w_int += __shfl_xor(w_int, o, kWave);
+    w_bor += __shfl_xor(w_bor, o, kWave);
+  }
+  if (lane == 0) {
+    const size_t o = (size_t)inst * nb_cap + j;
+    if (pstate != nullptr) pstate[o] = w_int;
+    pred[o] = W.b3[0] + (w_int + w_bor) / (float)H;
+  }
+}
+
+template <int C1, int C2>
+hipError_t run_columns(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist, int newest_slot,
+                       int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st) {
+  predict_columns_kernel<C1, C2><<<dim3(nb_cur - col_begin, ninst), kWave, 0, st>>>(
+      hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, col_begin, pstate, pred);
+  return hipGetLastError();
+}
+
 template <int C1, int C2>
 hipError_t run_full(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist, int newest_slot,
                     int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st) {
@@ -530,6 +607,18 @@ hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dwe
     return run_full<8, 8>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
   if (s.c1 == 16 && s.c2 == 32)
     return run_full<16, 32>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_predict_columns(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                                  int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred,
+                                  hipStream_t st) {
+  if (s.c1 == 4 && s.c2 == 4)
+    return run_columns<4, 4>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
+  if (s.c1 == 8 && s.c2 == 8)
+    return run_columns<8, 8>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
+  if (s.c1 == 16 && s.c2 == 32)
+    return run_columns<16, 32>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
   return hipErrorInvalidValue;
 }
 
