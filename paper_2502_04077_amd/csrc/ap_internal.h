@@ -37,7 +37,6 @@ struct WsLayout {
   size_t part_bmp;    // [n_inst][g][k]                 per selected block: max prob relative to split max
   size_t cal_ml;      // [n_inst][calib_chunks][g][2]
   size_t cal_bmp;     // [n_inst][g][nb_cap]
-  size_t row_tmp;     // [n_inst][nb_cap]               unused by the fused step
   size_t total;       // floats
 };
 

@@ -22,7 +22,6 @@ WsLayout ws_layout(const Shape& s) {
   w.part_bmp = o; o = align4(o + (size_t)s.n_inst * s.g * s.k);
   w.cal_ml = o;   o = align4(o + (size_t)s.n_inst * s.calib_chunks * s.g * 2);
   w.cal_bmp = o;  o = align4(o + (size_t)s.n_inst * s.g * s.nb_cap);
-  w.row_tmp = o;  o = align4(o + (size_t)s.n_inst * s.nb_cap);
   w.total = o;
   return w;
 }

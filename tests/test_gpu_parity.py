@@ -456,3 +456,27 @@ def test_fullsize_cfg4_sampled():
     st = lockstep(w, dev, w.steps, sample=[0, 2500, 4095], fused_every=1, warm_checks=(-1,))
     print("cfg4 full-size lock-step:", st)
     assert st["checked"] == 12
+
+
+def test_repeated_step_is_bitwise_deterministic():
+    """The same call on the same inputs gives the same bytes (split partials are merged in a fixed order)."""
+    dev = _dev()
+    for kw in (dict(kv_heads=3, t0=3000, budget_tokens=1024), dict(kv_heads=8, batch=130, t0=700, budget_tokens=256)):
+        w = small("det", g=4, head_dim=128, hist_len=16, **kw)
+        run = _run(w, dev)
+        K, V = kv_cache(w, dev)
+        for j in range(w.hist_len):
+            run.warmup_calibrate(queries(w, j - w.hist_len, dev), K, w.t0 - w.hist_len + 1 + j)
+        q = queries(w, 0, dev)
+        t = w.t_at(0)
+        hist0, n0 = run.hist.clone(), run.n_pushed
+        results = []
+        for _ in range(3):
+            run.hist.copy_(hist0)
+            run.n_pushed, run.state_n, run.state_t = n0, None, None
+            run.step(q, K, V, t)
+            torch.cuda.synchronize()
+            results.append((run.out.clone(), run.idx.clone(), run.pred.clone(), run.hist.clone()))
+        for r in results[1:]:
+            for a, b in zip(results[0], r):
+                assert torch.equal(a, b)
