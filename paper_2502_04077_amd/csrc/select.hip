@@ -5,6 +5,8 @@
 // and how many scores equal to T are still needed.  A final ordered sweep keeps every block with
 // key > T and the first `need` blocks with key == T, compacting in index order, so the output is
 // ascending and equal scores go to the lower index.  Integer work only: the result is exact.
+// When the candidates fit (up to 32 per thread) their keys are fetched once into registers, so the five
+// passes do not each wait on memory; longer rows are re-read from cache in every pass.
 #include "ap_internal.h"
 
 namespace ap {
@@ -37,6 +39,7 @@ __device__ inline void hist_add(uint32_t* hist, uint32_t bin, bool active) {
   if (active) atomicAdd(&hist[bin], 1u);
 }
 
+template <int KPT>   // keys per thread held in registers; 0 = re-read the scores in every pass
 __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* __restrict__ pred, int nb_cap,
                                                                   int nb_cur, int k, int n_sink, int n_local,
                                                                   int inst0, int32_t* __restrict__ idx,
@@ -59,20 +62,33 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
   const int lo = n_sink, hi = nb_cur - n_local;         // candidates [lo, hi), hi - lo > k_mid
   const int k_mid = k - n_sink - n_local;
 
+  // Candidate i of thread tid is block lo + i * kSelThreads + tid; past the end the key is a sentinel that
+  // no pass counts (valid is false).
+  constexpr int NK = KPT > 0 ? KPT : 1;
+  uint32_t keys[NK];
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const int j = lo + i * kSelThreads + tid;
+      keys[i] = score_key(p[min(j, hi - 1)]);
+    }
+  }
+  auto key_at = [&](int i, int j) -> uint32_t {
+    if constexpr (KPT > 0) return keys[i]; else return score_key(p[min(j, hi - 1)]);
+  };
+  const int n_iter = KPT > 0 ? KPT : (hi - lo + kSelThreads - 1) / kSelThreads;
+
   uint32_t prefix = 0;                                  // high bits of T found so far
   uint32_t need = (uint32_t)k_mid;                      // still to take among keys matching prefix
   if (k_mid > 0) {
     for (int shift = 24; shift >= 0; shift -= 8) {
       s_hist[tid] = 0;
       __syncthreads();
-      for (int jb = lo; jb < hi; jb += kSelThreads) {        // uniform trip count: ballots need every lane
-        const int j = jb + tid;
-        uint32_t key = 0;
-        bool match = false;
-        if (j < hi) {
-          key = score_key(p[j]);
-          match = (shift == 24) || ((key >> (shift + 8)) == prefix);
-        }
+#pragma unroll NK
+      for (int i = 0; i < n_iter; ++i) {                   // uniform trip count: ballots need every lane
+        const int j = lo + i * kSelThreads + tid;
+        const uint32_t key = key_at(i, j);
+        const bool match = j < hi && ((shift == 24) || ((key >> (shift + 8)) == prefix));
         hist_add(s_hist, (key >> shift) & 255u, match);
       }
       __syncthreads();
@@ -102,11 +118,13 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
   // Ordered sweep in chunks of one workgroup width.
   uint32_t taken = 0;                                   // selected so far (all threads agree)
   uint32_t eq_seen = 0;                                 // keys == T seen so far
-  for (int base = lo; base < hi && k_mid > 0; base += kSelThreads) {
-    const int j = base + tid;
+#pragma unroll NK
+  for (int i = 0; i < n_iter; ++i) {
+    if (k_mid <= 0) break;
+    const int j = lo + i * kSelThreads + tid;
     bool gt = false, eq = false;
     if (j < hi) {
-      const uint32_t key = score_key(p[j]);
+      const uint32_t key = key_at(i, j);
       gt = key > T;
       eq = key == T;
     }
@@ -139,8 +157,15 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
 
 hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred, int nb_cur, int32_t* idx,
                          int32_t* cnt, hipStream_t st) {
-  select_topk_kernel<<<dim3(ninst), kSelThreads, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local, inst0,
-                                                          idx, cnt);
+  const int n_mid = nb_cur - s.n_sink - s.n_local;
+  const dim3 grid(ninst);
+#define AP_SELECT(KPT) \
+  select_topk_kernel<KPT><<<grid, kSelThreads, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local, inst0, idx, cnt)
+  if (n_mid <= 8 * kSelThreads) AP_SELECT(8);
+  else if (n_mid <= 16 * kSelThreads) AP_SELECT(16);
+  else if (n_mid <= 32 * kSelThreads) AP_SELECT(32);
+  else AP_SELECT(0);
+#undef AP_SELECT
   return hipGetLastError();
 }
 
