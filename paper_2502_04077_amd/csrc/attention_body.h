@@ -1,0 +1,384 @@
+// Block-sparse GQA decode attention and dense calibration for gfx950.
+//
+// Both kernels share the same first two phases:
+//   1. logits  l[h][tok] = (q_h . K_tok) / sqrt(d) for the tokens of a list of blocks, fp32
+//      accumulate, written to LDS (tokens at or beyond t_cur get -inf);
+//   2. per head: M = max l, p = exp(l - M) in place, L = sum p; per (head, block) the max p.
+// The sparse kernel continues with  3. acc[h][:] = sum_tok p[h][tok] * V_tok  and either finishes
+// (one workgroup per instance) or leaves (M, L, acc, block maxima) for the combine kernel.
+// Softmax definition: Sec. 3.1; block max-pooling of the probabilities: Algorithm 1 steps 1-2
+// (softmax is monotone, so the pooled probability of a block is exp(max logit - M) / L).
+//
+// Memory access: a K or V row is d * sizeof(T) bytes (256 B for bf16, d = 128).  LPT = row bytes / 16
+// adjacent lanes read one row with one 16-byte load each, so every load instruction of a wave covers
+// 64 / LPT whole rows = 1 KiB of contiguous memory inside a block.
+#pragma once
+
+#include <type_traits>
+
+#include "ap_internal.h"
+
+namespace ap {
+namespace {
+
+
+struct bf16_t { uint16_t bits; };
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+template <typename T> struct KvT;
+template <> struct KvT<float> { static constexpr int E = 4; };
+template <> struct KvT<bf16_t> { static constexpr int E = 8; };
+
+__device__ inline void unpack16(const uint4& w, float (&f)[4], float) {
+  f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
+  f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
+}
+__device__ inline void unpack16(const uint4& w, float (&f)[8], bf16_t) {
+  f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
+  f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
+  f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
+  f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
+}
+
+// V rows are read once per call, a whole row per load instruction: 16-byte non-temporal loads keep them from
+// displacing data that is re-used from cache.  (K rows are read as two half-lines by consecutive MFMA
+// K-steps and are left to the cache: non-temporal K loads measured 9 % slower in the calibration kernel.)
+template <typename T> __device__ inline uint4 ld_stream(const T* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <int CTRL> __device__ inline float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the LPT adjacent lanes that share one token; every lane of the group gets the total.
+template <int LPT> __device__ inline float lane_group_sum(float v) {
+  v += dpp_move<0xB1>(v);                       // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);                       // quad_perm [2,3,0,1]
+  if (LPT >= 8) v += dpp_move<0x141>(v);        // row_half_mirror: pairs the two quads of 8 lanes
+  if (LPT >= 16) v += dpp_move<0x140>(v);       // row_mirror: pairs the two halves of 16 lanes
+  if (LPT >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T, int D, int G> struct Geom {
+  static constexpr int E = KvT<T>::E;           // elements per 16-byte load
+  static constexpr int LPT = D / E;             // lanes per token row
+  static constexpr int TPI = kWave / LPT;       // token rows per load instruction
+  static constexpr int NL = kGroupTokens / TPI; // load instructions per 16-token group
+  static_assert(LPT >= 8 && LPT <= 32 && G <= LPT, "unsupported geometry");
+};
+
+// Phase 1.  `block_of(jb)` gives the block index of list position jb.  s_p is [G][ld].
+//
+// bf16: the g x d by d x 16-token contraction runs on v_mfma_f32_16x16x32_bf16 (A = 16 K rows, B = q^T
+// padded to 16 columns, fp32 accumulate); with VALU dot products plus cross-lane sums the kernel spends
+// two thirds of its issue slots on arithmetic and cannot keep HBM busy.  Lane l supplies token l % 16
+// straight from global memory.  The order of the contraction index is free as long as A and B agree, so
+// lane group g = l / 16 takes dims g d/4 .. (g+1) d/4 - 1, eight per K-step: every lane reads 64
+// contiguous bytes over the four steps and the four groups together cover the whole 256-byte row.
+// D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so lanes with head < G hold the logits.
+// fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
+template <typename T, int D, int G, class BlockOf>
+__device__ inline void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
+                                 int t_cur, int ntok, BlockOf block_of, float* s_p, int ld) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const float scale = rsqrtf((float)D);
+  const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    constexpr int KS = D / 32;
+    const int row = lane & 15, g = lane >> 4;
+    bf16x8 qb[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      uint4 w = make_uint4(0, 0, 0, 0);
+      if (row < G) w = *reinterpret_cast<const uint4*>(q_inst + (size_t)row * D + g * (D / 4) + s * 8);
+      qb[s] = __builtin_bit_cast(bf16x8, w);
+    }
+    auto load_group = [&](int grp, uint4 (&kw)[KS]) {
+      const int tau = grp * kGroupTokens + row;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
+      if (tau < ntok) {
+        const int gtok = block_of(tau >> log2b) * b + (tau & (b - 1));
+        const T* src = K_inst + (size_t)gtok * D + g * (D / 4);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kw[s] = *reinterpret_cast<const uint4*>(src + s * 8);
+      }
+    };
+    uint4 cur[KS], nxt[KS];
+    if (wave < ngroups) load_group(wave, cur);
+    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      const bool more = grp + kAttnWaves < ngroups;
+      if (more) load_group(grp + kAttnWaves, nxt);
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[s]), qb[s], acc, 0, 0, 0);
+      const int tau0 = grp * kGroupTokens + 4 * g;       // four tokens of one block (b is a multiple of 8)
+      if (row < G && tau0 < ntok) {
+        const int gtok0 = block_of(tau0 >> log2b) * b + (tau0 & (b - 1));
+        float4 o;
+        o.x = gtok0 + 0 < t_cur ? acc[0] * scale : -INFINITY;
+        o.y = gtok0 + 1 < t_cur ? acc[1] * scale : -INFINITY;
+        o.z = gtok0 + 2 < t_cur ? acc[2] * scale : -INFINITY;
+        o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
+        *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
+      }
+      if (more) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) cur[s] = nxt[s];
+      }
+    }
+  } else {
+    using Ge = Geom<T, D, G>;
+    constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
+    const int dpart = lane % LPT;
+    const int tslot = lane / LPT;
+    float qr[G][E];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      static_assert(E * sizeof(T) == 16, "one 16-byte load per lane");
+      uint4 w = *reinterpret_cast<const uint4*>(q_inst + (size_t)h * D + dpart * E);
+      float f[E];
+      unpack16(w, f, T{});
+#pragma unroll
+      for (int e = 0; e < E; ++e) qr[h][e] = f[e] * scale;
+    }
+    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      uint4 kw[NL];
+      int gtok[NL];
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int tau = grp * kGroupTokens + i * TPI + tslot;
+        kw[i] = make_uint4(0, 0, 0, 0);
+        gtok[i] = -1;
+        if (tau < ntok) {
+          const int blk = block_of(tau >> log2b);
+          gtok[i] = blk * b + (tau & (b - 1));
+          kw[i] = *reinterpret_cast<const uint4*>(K_inst + (size_t)gtok[i] * D + dpart * E);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int tau = grp * kGroupTokens + i * TPI + tslot;
+        float kf[E];
+        unpack16(kw[i], kf, T{});
+        float mine = 0.f;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          float sdot = 0.f;
+#pragma unroll
+          for (int e = 0; e < E; ++e) sdot = fmaf(qr[h][e], kf[e], sdot);
+          sdot = lane_group_sum<LPT>(sdot);
+          if (dpart == h) mine = sdot;
+        }
+        if (dpart < G && tau < ntok) s_p[dpart * ld + tau] = (gtok[i] < t_cur) ? mine : -INFINITY;
+      }
+    }
+  }
+}
+
+// Phase 2.  Leaves p in s_p, (M, L) in s_m / s_l, per (head, block) max p in s_bmp[h * nblk + jb].
+template <int G>
+__device__ inline void softmax_stats(float* s_p, int ld, int ntok, int b, int nblk, float* s_m, float* s_l,
+                                     float* s_bmp) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  for (int h = wave; h < G; h += kAttnWaves) {
+    float m = -INFINITY;
+    for (int tau = lane; tau < ntok; tau += kWave) m = fmaxf(m, s_p[h * ld + tau]);
+    m = wave_max(m);
+    float sum = 0.f;
+    for (int tau = lane; tau < ntok; tau += kWave) {
+      const float p = __expf(s_p[h * ld + tau] - m);
+      s_p[h * ld + tau] = p;
+      sum += p;
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) { s_m[h] = m; s_l[h] = sum; }
+  }
+  __syncthreads();
+  for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+    const int h = pair / nblk, jb = pair - h * nblk;
+    const int t0 = jb * b;
+    const int t1 = min(t0 + b, ntok);
+    float mx = 0.f;
+    for (int tau = t0; tau < t1; ++tau) mx = fmaxf(mx, s_p[h * ld + tau]);
+    s_bmp[pair] = mx;
+  }
+  __syncthreads();
+}
+
+// Writes one instance's pooled row: rowval[pos] at column idx[pos] (idx ascending), 0 elsewhere.
+__device__ inline void write_row(float* __restrict__ row, int nb_cap, const int* s_idx, int cnt,
+                                 const float* s_rowval) {
+  for (int j = threadIdx.x; j < nb_cap; j += blockDim.x) {
+    int lo = 0, hi = cnt;                       // first position with idx >= j
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (s_idx[mid] < j) lo = mid + 1; else hi = mid;
+    }
+    row[j] = (lo < cnt && s_idx[lo] == j) ? s_rowval[lo] : 0.f;
+  }
+}
+
+struct SparseArgs {
+  const void* q; const void* K; const void* V;
+  const int32_t* idx; const int32_t* cnt;
+  float* out; float* row; size_t row_stride;
+  float* part_ml; float* part_acc; float* part_bmp;
+  int t_cap, nb_cap, k, b, log2b, t_cur, nb_cur, n_split, blk_per_split, inst0;
+};
+
+// Sparse decode of instance `inst`, split `split`, by one workgroup of kAttnThreads threads.
+// smem: sparse_lds_floats(...) floats of LDS, 16-byte aligned.
+template <typename T, int D, int G>
+__device__ inline void sparse_decode_body(const SparseArgs& a, int inst, int split, float* smem) {
+  using Ge = Geom<T, D, G>;
+  constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int dpart = lane % LPT, tslot = lane / LPT;
+
+  const int cnt = min(max(a.cnt[inst], 0), a.k);
+  // With one workgroup per instance the whole list is local; otherwise this split's slice.
+  const int j0 = (a.n_split == 1) ? 0 : min(cnt, split * a.blk_per_split);
+  const int j1 = (a.n_split == 1) ? cnt : min(cnt, j0 + a.blk_per_split);
+  const int nblk = j1 - j0;
+  const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
+  const int ld = nblk_cap * a.b;
+  const int ntok = nblk * a.b;
+
+  float* s_p = smem;                                   // [G][ld]
+  float* s_acc = s_p + G * ld;                         // [waves][G][D]
+  float* s_bmp = s_acc + kAttnWaves * G * D;           // [G][nblk_cap]
+  float* s_rowval = s_bmp + G * nblk_cap;              // [nblk_cap]
+  float* s_m = s_rowval + nblk_cap;                    // [G]
+  float* s_l = s_m + G;                                // [G]
+  int* s_idx = reinterpret_cast<int*>(s_l + G);        // [nblk_cap]
+
+  for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
+    s_idx[j] = min(max(a.idx[(size_t)inst * a.k + j0 + j], 0), a.nb_cur - 1);
+  __syncthreads();
+
+  const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
+  const T* K_inst = static_cast<const T*>(a.K) + (size_t)inst * a.t_cap * D;
+  const T* V_inst = static_cast<const T*>(a.V) + (size_t)inst * a.t_cap * D;
+
+  float acc[G][E];
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
+
+  if (nblk > 0) {
+    qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; }, s_p, ld);
+    __syncthreads();
+    softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
+
+    // Phase 3: acc += p * V, same token-to-lane mapping as phase 1.
+    const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      uint4 vw[NL];
+      int tau_i[NL];
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int tau = grp * kGroupTokens + i * TPI + tslot;
+        tau_i[i] = tau < ntok ? tau : -1;
+        vw[i] = make_uint4(0, 0, 0, 0);
+        if (tau < ntok) {
+          const int gtok = s_idx[tau >> a.log2b] * a.b + (tau & (a.b - 1));
+          vw[i] = ld_stream(V_inst + (size_t)gtok * D + dpart * E);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        float vf[E];
+        unpack16(vw[i], vf, T{});
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          const float p = tau_i[i] >= 0 ? s_p[h * ld + tau_i[i]] : 0.f;
+#pragma unroll
+          for (int e = 0; e < E; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
+        }
+      }
+    }
+  } else {
+    if (threadIdx.x < G) { s_m[threadIdx.x] = -INFINITY; s_l[threadIdx.x] = 0.f; }
+  }
+
+  // Sum the token slots of a wave (lanes that hold the same dims), then the waves through LDS.
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      float v = acc[h][e];
+#pragma unroll
+      for (int o = LPT; o < kWave; o <<= 1) v += __shfl_xor(v, o, 64);
+      acc[h][e] = v;
+    }
+  if (tslot == 0) {
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+      for (int e = 0; e < E; ++e) s_acc[(wave * G + h) * D + dpart * E + e] = acc[h][e];
+  }
+  __syncthreads();
+
+  if (a.n_split == 1) {
+    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
+      a.out[(size_t)inst * G * D + o] = v / s_l[o / D];
+    }
+    for (int jb = threadIdx.x; jb < nblk; jb += kAttnThreads) {
+      float mx = 0.f;
+#pragma unroll
+      for (int h = 0; h < G; ++h) mx = fmaxf(mx, s_bmp[h * nblk + jb] / s_l[h]);
+      s_rowval[jb] = mx;
+    }
+    __syncthreads();
+    write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, nblk, s_rowval);
+  } else {
+    const size_t ps = (size_t)inst * a.n_split + split;
+    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
+      a.part_acc[ps * G * D + o] = v;
+    }
+    if (threadIdx.x < G) {
+      a.part_ml[(ps * G + threadIdx.x) * 2 + 0] = s_m[threadIdx.x];
+      a.part_ml[(ps * G + threadIdx.x) * 2 + 1] = s_l[threadIdx.x];
+    }
+    for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+      const int h = pair / nblk, jb = pair - h * nblk;
+      a.part_bmp[((size_t)inst * G + h) * a.k + j0 + jb] = s_bmp[pair];
+    }
+  }
+}
+
+
+// LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens.
+template <int D, int G> inline size_t sparse_lds_floats(int nblk_cap, int b) {
+  return (size_t)G * nblk_cap * b + kAttnWaves * G * D + (size_t)G * nblk_cap + nblk_cap + 2 * G + nblk_cap;
+}
+
+}  // namespace
+}  // namespace ap
