@@ -30,11 +30,11 @@ template <typename T> struct KvT;
 template <> struct KvT<float> { static constexpr int E = 4; };
 template <> struct KvT<bf16_t> { static constexpr int E = 8; };
 
-__device__ inline void unpack16(const uint4& w, float (&f)[4], float) {
+__device__ __forceinline__ void unpack16(const uint4& w, float (&f)[4], float) {
   f[0] = __uint_as_float(w.x); f[1] = __uint_as_float(w.y);
   f[2] = __uint_as_float(w.z); f[3] = __uint_as_float(w.w);
 }
-__device__ inline void unpack16(const uint4& w, float (&f)[8], bf16_t) {
+__device__ __forceinline__ void unpack16(const uint4& w, float (&f)[8], bf16_t) {
   f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
   f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
   f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
@@ -44,18 +44,18 @@ __device__ inline void unpack16(const uint4& w, float (&f)[8], bf16_t) {
 // V rows are read once per call, a whole row per load instruction: 16-byte non-temporal loads keep them from
 // displacing data that is re-used from cache.  (K rows are read as two half-lines by consecutive MFMA
 // K-steps and are left to the cache: non-temporal K loads measured 9 % slower in the calibration kernel.)
-template <typename T> __device__ inline uint4 ld_stream(const T* p) {
+template <typename T> __device__ __forceinline__ uint4 ld_stream(const T* p) {
   typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-template <int CTRL> __device__ inline float dpp_move(float v) {
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
 // Sum over the LPT adjacent lanes that share one token; every lane of the group gets the total.
-template <int LPT> __device__ inline float lane_group_sum(float v) {
+template <int LPT> __device__ __forceinline__ float lane_group_sum(float v) {
   v += dpp_move<0xB1>(v);                       // quad_perm [1,0,3,2]
   v += dpp_move<0x4E>(v);                       // quad_perm [2,3,0,1]
   if (LPT >= 8) v += dpp_move<0x141>(v);        // row_half_mirror: pairs the two quads of 8 lanes
@@ -64,12 +64,12 @@ template <int LPT> __device__ inline float lane_group_sum(float v) {
   return v;
 }
 
-__device__ inline float wave_max(float v) {
+__device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
   return v;
 }
-__device__ inline float wave_sum(float v) {
+__device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
@@ -94,7 +94,7 @@ template <typename T, int D, int G> struct Geom {
 // D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so lanes with head < G hold the logits.
 // fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
 template <typename T, int D, int G, class BlockOf>
-__device__ inline void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
+__device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
                                  int t_cur, int ntok, BlockOf block_of, float* s_p, int ld) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -110,7 +110,7 @@ __device__ inline void qk_logits(const T* __restrict__ q_inst, const T* __restri
       if (row < G) w = *reinterpret_cast<const uint4*>(q_inst + (size_t)row * D + g * (D / 4) + s * 8);
       qb[s] = __builtin_bit_cast(bf16x8, w);
     }
-    auto load_group = [&](int grp, uint4 (&kw)[KS]) {
+    auto load_group = [&](int grp, uint4 (&kw)[KS]) __attribute__((always_inline)) {
       const int tau = grp * kGroupTokens + row;
 #pragma unroll
       for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
@@ -196,7 +196,7 @@ __device__ inline void qk_logits(const T* __restrict__ q_inst, const T* __restri
 
 // Phase 2.  Leaves p in s_p, (M, L) in s_m / s_l, per (head, block) max p in s_bmp[h * nblk + jb].
 template <int G>
-__device__ inline void softmax_stats(float* s_p, int ld, int ntok, int b, int nblk, float* s_m, float* s_l,
+__device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int b, int nblk, float* s_m, float* s_l,
                                      float* s_bmp) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -226,7 +226,7 @@ __device__ inline void softmax_stats(float* s_p, int ld, int ntok, int b, int nb
 }
 
 // Writes one instance's pooled row: rowval[pos] at column idx[pos] (idx ascending), 0 elsewhere.
-__device__ inline void write_row(float* __restrict__ row, int nb_cap, const int* s_idx, int cnt,
+__device__ __forceinline__ void write_row(float* __restrict__ row, int nb_cap, const int* s_idx, int cnt,
                                  const float* s_rowval) {
   for (int j = threadIdx.x; j < nb_cap; j += blockDim.x) {
     int lo = 0, hi = cnt;                       // first position with idx >= j
@@ -249,7 +249,7 @@ struct SparseArgs {
 // Sparse decode of instance `inst`, split `split`, by one workgroup of kAttnThreads threads.
 // smem: sparse_lds_floats(...) floats of LDS, 16-byte aligned.
 template <typename T, int D, int G>
-__device__ inline void sparse_decode_body(const SparseArgs& a, int inst, int split, float* smem) {
+__device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst, int split, float* smem) {
   using Ge = Geom<T, D, G>;
   constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;

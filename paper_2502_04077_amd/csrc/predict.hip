@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
 //         a time; see predict_inc_mfma_kernel.
 
 template <int C1, int C2, int HF>
-__device__ inline void y2_valu(const Weights<C1, C2>& W, const float* yb, int YW, float (&o)[3][C2]) {
+__device__ __forceinline__ void y2_valu(const Weights<C1, C2>& W, const float* yb, int YW, float (&o)[3][C2]) {
 #pragma unroll
   for (int k = 0; k < 3; ++k)
 #pragma unroll
@@ -173,7 +173,7 @@ __device__ inline void y2_valu(const Weights<C1, C2>& W, const float* yb, int YW
 
 // Stages x rows -1..3 (half 0) and H-5..H-1 (half 1), columns c0-2 .. c0-2+XW-1, zero outside the tile.
 template <int XW, int NW>
-__device__ inline void stage_x_rows(float* s_x, const float* hist_inst, int newest_slot, int H, int R, int nb_cap,
+__device__ __forceinline__ void stage_x_rows(float* s_x, const float* hist_inst, int newest_slot, int H, int R, int nb_cap,
                                     int nb_cur, int c0) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   for (int rr = wave; rr < 10; rr += NW) {
@@ -189,7 +189,7 @@ __device__ inline void stage_x_rows(float* s_x, const float* hist_inst, int newe
 
 // Writes state and pred for column c0 + tid from the four head-weighted partial sums in s_red[2][2][LD].
 template <int LD>
-__device__ inline void finish_column(const float* s_red, int tid, size_t o, int advance, float b3, int H,
+__device__ __forceinline__ void finish_column(const float* s_red, int tid, size_t o, int advance, float b3, int H,
                                      float* pstate, float* pred) {
   float st = pstate[o];
   if (advance) {
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
   __syncthreads();
   // y1: thread (half, column) evaluates its four rows q0..q3; the two halo columns of each (half, q) are
   // done by 16 threads in a second pass.
-  auto y1_at = [&](int hf, int q, int yc) {
+  auto y1_at = [&](int hf, int q, int yc) __attribute__((always_inline)) {
     const int j = c0 - 1 + yc;
     // first staged x row of the 3-row window, and the tap row that lies outside the history window
     const int base = (hf == 0 && q == 3) ? 0 : q;

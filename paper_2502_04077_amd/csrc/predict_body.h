@@ -17,7 +17,7 @@ constexpr int kYR = kTS + 2;            // y1 rows staged per strip
 
 typedef const float __attribute__((address_space(4))) * const_f32_ptr;
 
-__device__ inline const_f32_ptr as_constant(const float* p) {
+__device__ __forceinline__ const_f32_ptr as_constant(const float* p) {
   return (const_f32_ptr)(uintptr_t)p;   // weights never change during a launch: read through the scalar cache
 }
 
@@ -34,14 +34,14 @@ template <int C1, int C2> struct Weights {
   }
 };
 
-__device__ inline int ring_slot(int newest_slot, int H, int R, int r) {
+__device__ __forceinline__ int ring_slot(int newest_slot, int H, int R, int r) {
   int slot = (newest_slot - (H - 1 - r)) % R;   // logical row r (H-1 = newest, -1 = the row that just left)
   return slot < 0 ? slot + R : slot;
 }
 
 // One y1 pixel, all C1 channels, from a 3x3 x neighbourhood.
 template <int C1, int C2>
-__device__ inline void y1_pixel(const Weights<C1, C2>& W, const float (&x)[3][3], bool inside, float* dst,
+__device__ __forceinline__ void y1_pixel(const Weights<C1, C2>& W, const float (&x)[3][3], bool inside, float* dst,
                                 int chan_stride) {
 #pragma unroll
   for (int c = 0; c < C1; ++c) {
@@ -79,7 +79,7 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 constexpr int kPredMfmaLdsFloats = 2 * 4 * 128 * 4 + 2 * (2 * 5 * 130 + 12) + 4 * 128;
 
 // Workgroup `chunk` of `n_chunks` of instance `inst` (256 threads); smem: kPredMfmaLdsFloats floats, 16-byte aligned.
-__device__ inline void predict_inc_mfma_body(const float* __restrict__ hist, const float* __restrict__ wts_global,
+__device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ hist, const float* __restrict__ wts_global,
                                              int R, int H, int newest_slot, int nb_cur, int nb_cap, int inst,
                                              int chunk, int n_chunks, int advance, float* __restrict__ pstate,
                                              float* __restrict__ pred, float* smem) {
@@ -136,7 +136,7 @@ __device__ inline void predict_inc_mfma_body(const float* __restrict__ hist, con
   float xpre[9], pst_cur = 0.f, pst_next = 0.f;
   // Loads are unconditional on clamped addresses (no divergent branches); the raw values stay untouched in
   // registers until `stash` masks them, so nothing waits on them while the current tile is computed.
-  auto fetch = [&](int tile, float& pst) {
+  auto fetch = [&](int tile, float& pst) __attribute__((always_inline)) {
     const int c0 = tile * IW;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
@@ -144,7 +144,7 @@ __device__ inline void predict_inc_mfma_body(const float* __restrict__ hist, con
       for (int c = 0; c < 3; ++c) xpre[i * 3 + c] = xsrc[i][min(max(c0 - 2 + lane + kWave * c, 0), nb_cur - 1)];
     pst = pstate_inst[min(c0 + tid, nb_cur - 1)];
   };
-  auto stash = [&](int tile, float* s_x) {
+  auto stash = [&](int tile, float* s_x) __attribute__((always_inline)) {
     const int c0 = tile * IW;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
@@ -158,6 +158,7 @@ __device__ inline void predict_inc_mfma_body(const float* __restrict__ hist, con
   stash(t_begin, s_xb);
   __syncthreads();
 
+#pragma unroll 1
   for (int tile = t_begin; tile < t_end; ++tile) {
     const int c0 = tile * IW;
     const float* s_x = s_xb + ((tile - t_begin) & 1) * XBUF;

@@ -19,7 +19,7 @@ constexpr int kSelScratchWords = 256 + 3 * (256 / kWave) + 4;
 constexpr int kSelThreads = 256;
 constexpr int kSelWaves = kSelThreads / kWave;
 
-__device__ inline uint32_t score_key(float x) {
+__device__ __forceinline__ uint32_t score_key(float x) {
   uint32_t u = __float_as_uint(x);
   if (u == 0x80000000u) u = 0u;                         // -0 ranks with +0
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);    // larger score <=> larger key
@@ -28,7 +28,7 @@ __device__ inline uint32_t score_key(float x) {
 // Adds one to hist[bin] for every lane with `active`.  Predicted scores of neighbouring blocks are close,
 // so most lanes of a wave share a bin and per-lane LDS atomics would serialise on it: the two most common
 // leading bins are counted with a ballot and added once per wave, the rest fall back to single adds.
-__device__ inline void hist_add(uint32_t* hist, uint32_t bin, bool active) {
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool active) {
   const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
   for (int round = 0; round < 2; ++round) {
@@ -48,7 +48,7 @@ __device__ inline void hist_add(uint32_t* hist, uint32_t bin, bool active) {
 //   out      the instance's k index slots, cnt_out its count
 //   s_mem    kSelScratchWords words of LDS, free for this call (the caller synchronises before)
 template <int KPT>   // keys per thread held in registers; 0 = re-read the scores in every pass
-__device__ inline void select_topk_body(const float* __restrict__ p, int nb_cur, int k, int n_sink, int n_local,
+__device__ __forceinline__ void select_topk_body(const float* __restrict__ p, int nb_cur, int k, int n_sink, int n_local,
                                         int32_t* __restrict__ out, int32_t* __restrict__ cnt_out, uint32_t* s_mem) {
   uint32_t* s_hist = s_mem;                     // [256]
   uint32_t* s_wsum = s_mem + 256;               // [kSelWaves]
@@ -77,7 +77,7 @@ __device__ inline void select_topk_body(const float* __restrict__ p, int nb_cur,
       keys[i] = score_key(p[min(j, hi - 1)]);
     }
   }
-  auto key_at = [&](int i, int j) -> uint32_t {
+  auto key_at = [&](int i, int j) __attribute__((always_inline)) -> uint32_t {
     if constexpr (KPT > 0) return keys[i]; else return score_key(p[min(j, hi - 1)]);
   };
   const int n_iter = KPT > 0 ? KPT : (hi - lo + kSelThreads - 1) / kSelThreads;
