@@ -96,6 +96,14 @@ int32_t ap_nb_cap(const ap_ctx* ctx);
  * copy on `stream`, so the caller may free the blob on return. */
 int ap_set_weights(ap_ctx* ctx, const float* host_blob, size_t n_floats, void* stream);
 
+/* Paged K/V cache (Sec. 2.1: the block-based sparsification also applies to paged attention).
+ * After this call the K and V arguments of ap_sparse_decode, ap_calibrate and ap_step are pools
+ * [n_phys_blocks][b][d] shared by all instances, and block_table[inst][nb_cap] (device int32,
+ * caller-owned, must stay valid; its contents may change between calls) gives the physical block of
+ * logical block j of an instance.  Entries are clamped into the pool.  History, scores and selected
+ * indices stay in logical block numbers.  block_table = NULL returns to the contiguous layout. */
+int ap_set_block_table(ap_ctx* ctx, const int32_t* block_table, int32_t n_phys_blocks);
+
 /* Algorithm 1 step 4: pred = F(A_H) on the H x nb_cur tile (zero outside it at every conv layer),
  * time average over H, raw linear head.
  *   hist      device float [n_inst][R][nb_cap]

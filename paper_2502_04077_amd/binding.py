@@ -19,7 +19,7 @@ AP_PRED_REBASE, AP_PRED_ADVANCE, AP_PRED_HOLD = 0, 1, 2
 AP_FLAG_PREDICTOR_FP32 = 1
 
 EXPORTS = [
-    "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights",
+    "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_set_block_table",
     "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
     "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
@@ -60,6 +60,7 @@ def load_library() -> C.CDLL:
     lib.ap_nb_cap.argtypes = [vp]
     lib.ap_nb_cap.restype = i32
     lib.ap_set_weights.argtypes = [vp, vp, sz, vp]
+    lib.ap_set_block_table.argtypes = [vp, vp, i32]
     lib.ap_predict.argtypes = [vp, vp, i64, i32, vp, vp, vp]
     lib.ap_predict_incremental.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.ap_select_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp]
@@ -141,6 +142,10 @@ class Context:
     def set_weights(self, blob: np.ndarray) -> None:
         blob = np.ascontiguousarray(blob, dtype=np.float32)
         _check(self._lib.ap_set_weights(self._h, blob.ctypes.data, blob.size, _stream()))
+
+    def set_block_table(self, table, n_phys_blocks: int = 0) -> None:
+        """table: device int32 [n_inst][nb_cap] (kept alive by the caller), or None for the contiguous layout."""
+        _check(self._lib.ap_set_block_table(self._h, None if table is None else _ptr(table), n_phys_blocks))
 
     def predict(self, hist, n_pushed, nb_cur, pred, ws) -> None:
         _check(self._lib.ap_predict(self._h, _ptr(hist), n_pushed, nb_cur, _ptr(pred), _ptr(ws), _stream()))

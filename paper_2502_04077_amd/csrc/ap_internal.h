@@ -28,6 +28,8 @@ struct Shape {
   int predictor_mfma; // second conv layer of the incremental predictor on f16 MFMA (8/8 channels only)
   int n_split;        // workgroups per instance in sparse decode
   int calib_chunks;   // max workgroups per instance in calibrate
+  const int32_t* table;  // device block table of a paged K/V cache [n_inst][nb_cap], or null (caller-owned)
+  int n_phys;            // physical blocks in the pool
 };
 
 // Workspace carve-up (float offsets from ws).

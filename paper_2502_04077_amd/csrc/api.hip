@@ -83,6 +83,8 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   const int chunk_blocks = ap::kCalibChunkTokens / s.b;
   s.calib_chunks = (s.nb_cap + chunk_blocks - 1) / chunk_blocks;
   if ((size_t)s.calib_chunks * s.g * sizeof(float) > 60000) { delete ctx; return AP_ERR_UNSUPPORTED; }
+  s.table = nullptr;
+  s.n_phys = 0;
   ctx->dweights = nullptr;
   ctx->have_weights = false;
   *out = ctx;
@@ -104,6 +106,20 @@ size_t ap_workspace_bytes(const ap_ctx* ctx) {
 
 int32_t ap_hist_slots(const ap_ctx* ctx) { return ctx ? ctx->s.R : 0; }
 int32_t ap_nb_cap(const ap_ctx* ctx) { return ctx ? ctx->s.nb_cap : 0; }
+
+int ap_set_block_table(ap_ctx* ctx, const int32_t* block_table, int32_t n_phys_blocks) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  if (block_table == nullptr) {
+    ctx->s.table = nullptr;
+    ctx->s.n_phys = 0;
+    return AP_OK;
+  }
+  if (!aligned16(block_table)) return AP_ERR_ALIGN;
+  if (n_phys_blocks < 1) return AP_ERR_ARG;
+  ctx->s.table = block_table;
+  ctx->s.n_phys = n_phys_blocks;
+  return AP_OK;
+}
 
 int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream) {
   if (ctx == nullptr || blob == nullptr) return AP_ERR_ARG;

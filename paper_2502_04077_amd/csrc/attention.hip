@@ -61,6 +61,8 @@ struct CalibArgs {
   const void* q; const void* K;
   float* row; float* cal_ml; float* cal_bmp;
   int t_cap, nb_cap, b, log2b, t_cur, nb_cur, chunk_blocks, n_chunks, chunk_slots;
+  const int32_t* table;
+  int n_phys;
 };
 
 template <typename T, int D, int G>
@@ -75,10 +77,15 @@ __global__ __launch_bounds__(kAttnThreads) void calibrate_kernel(CalibArgs a) {
   float* s_bmp = s_p + G * ld;          // [G][chunk_blocks]
   float* s_m = s_bmp + G * a.chunk_blocks;
   float* s_l = s_m + G;
+  int* s_phys = reinterpret_cast<int*>(s_l + G);   // [chunk_blocks] place of each block of the chunk in K
 
+  for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
+    s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + c0 + j], 0), a.n_phys - 1) : c0 + j;
+  __syncthreads();
   const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
-  const T* K_inst = static_cast<const T*>(a.K) + (size_t)inst * a.t_cap * D;
-  qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; }, s_p, ld);
+  const T* K_inst = static_cast<const T*>(a.K) + (a.table ? 0 : (size_t)inst * a.t_cap * D);
+  qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; },
+                     [&](int jb) { return s_phys[jb]; }, s_p, ld);
   __syncthreads();
   softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
   for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
@@ -141,7 +148,7 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
 
 template <typename T, int D, int G>
 hipError_t run_calib(const Shape& s, CalibArgs a, hipStream_t st) {
-  const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G);
+  const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G + a.chunk_blocks);
   calibrate_kernel<T, D, G><<<dim3(a.n_chunks, s.n_inst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -181,6 +188,7 @@ hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void
   a.n_split = s.n_split;
   a.blk_per_split = (s.k + s.n_split - 1) / s.n_split;
   a.inst0 = inst0;
+  a.table = s.table; a.n_phys = s.n_phys;
   AP_DISPATCH(run_sparse, s, ninst, a, st)
 }
 
@@ -194,6 +202,7 @@ hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_
   a.chunk_blocks = kCalibChunkTokens / s.b;
   a.n_chunks = (a.nb_cur + a.chunk_blocks - 1) / a.chunk_blocks;
   a.chunk_slots = s.calib_chunks;
+  a.table = s.table; a.n_phys = s.n_phys;
   AP_DISPATCH(run_calib, s, a, st)
 }
 

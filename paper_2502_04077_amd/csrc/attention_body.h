@@ -83,7 +83,8 @@ template <typename T, int D, int G> struct Geom {
   static_assert(LPT >= 8 && LPT <= 32 && G <= LPT, "unsupported geometry");
 };
 
-// Phase 1.  `block_of(jb)` gives the block index of list position jb.  s_p is [G][ld].
+// Phase 1.  `block_of(jb)` gives the logical block index of list position jb (its token positions decide the
+// causal mask), `phys_of(jb)` the block's place in K (the same unless a block table is in use).  s_p is [G][ld].
 //
 // bf16: the g x d by d x 16-token contraction runs on v_mfma_f32_16x16x32_bf16 (A = 16 K rows, B = q^T
 // padded to 16 columns, fp32 accumulate); with VALU dot products plus cross-lane sums the kernel spends
@@ -93,9 +94,9 @@ template <typename T, int D, int G> struct Geom {
 // contiguous bytes over the four steps and the four groups together cover the whole 256-byte row.
 // D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so lanes with head < G hold the logits.
 // fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
-template <typename T, int D, int G, class BlockOf>
+template <typename T, int D, int G, class BlockOf, class PhysOf>
 __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
-                                 int t_cur, int ntok, BlockOf block_of, float* s_p, int ld) {
+                                          int t_cur, int ntok, BlockOf block_of, PhysOf phys_of, float* s_p, int ld) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const float scale = rsqrtf((float)D);
@@ -115,8 +116,8 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
 #pragma unroll
       for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
       if (tau < ntok) {
-        const int gtok = block_of(tau >> log2b) * b + (tau & (b - 1));
-        const T* src = K_inst + (size_t)gtok * D + g * (D / 4);
+        const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
+        const T* src = K_inst + (size_t)ptok * D + g * (D / 4);
 #pragma unroll
         for (int s = 0; s < KS; ++s) kw[s] = *reinterpret_cast<const uint4*>(src + s * 8);
       }
@@ -169,9 +170,9 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
         kw[i] = make_uint4(0, 0, 0, 0);
         gtok[i] = -1;
         if (tau < ntok) {
-          const int blk = block_of(tau >> log2b);
-          gtok[i] = blk * b + (tau & (b - 1));
-          kw[i] = *reinterpret_cast<const uint4*>(K_inst + (size_t)gtok[i] * D + dpart * E);
+          gtok[i] = block_of(tau >> log2b) * b + (tau & (b - 1));
+          const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
+          kw[i] = *reinterpret_cast<const uint4*>(K_inst + (size_t)ptok * D + dpart * E);
         }
       }
 #pragma unroll
@@ -244,6 +245,8 @@ struct SparseArgs {
   float* out; float* row; size_t row_stride;
   float* part_ml; float* part_acc; float* part_bmp;
   int t_cap, nb_cap, k, b, log2b, t_cur, nb_cur, n_split, blk_per_split, inst0;
+  const int32_t* table;           // block table [n_inst][nb_cap] of a paged cache, or null
+  int n_phys;                     // blocks in the pool (table entries are clamped into it)
 };
 
 // Sparse decode of instance `inst`, split `split`, by one workgroup of kAttnThreads threads.
@@ -270,15 +273,21 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
   float* s_rowval = s_bmp + G * nblk_cap;              // [nblk_cap]
   float* s_m = s_rowval + nblk_cap;                    // [G]
   float* s_l = s_m + G;                                // [G]
-  int* s_idx = reinterpret_cast<int*>(s_l + G);        // [nblk_cap]
+  int* s_idx = reinterpret_cast<int*>(s_l + G);        // [nblk_cap] logical block of each list position
+  int* s_phys = s_idx + nblk_cap;                      // [nblk_cap] its place in K / V
 
-  for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
-    s_idx[j] = min(max(a.idx[(size_t)inst * a.k + j0 + j], 0), a.nb_cur - 1);
+  for (int j = threadIdx.x; j < nblk; j += kAttnThreads) {
+    const int blk = min(max(a.idx[(size_t)inst * a.k + j0 + j], 0), a.nb_cur - 1);
+    s_idx[j] = blk;
+    s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + blk], 0), a.n_phys - 1) : blk;
+  }
   __syncthreads();
 
+  // Contiguous cache: [n_inst][t_cap][d].  Paged cache: one pool [n_phys][b][d] for all instances.
+  const size_t kv_off = a.table ? 0 : (size_t)inst * a.t_cap * D;
   const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
-  const T* K_inst = static_cast<const T*>(a.K) + (size_t)inst * a.t_cap * D;
-  const T* V_inst = static_cast<const T*>(a.V) + (size_t)inst * a.t_cap * D;
+  const T* K_inst = static_cast<const T*>(a.K) + kv_off;
+  const T* V_inst = static_cast<const T*>(a.V) + kv_off;
 
   float acc[G][E];
 #pragma unroll
@@ -287,7 +296,8 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
 
   if (nblk > 0) {
-    qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; }, s_p, ld);
+    qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; },
+                       [&](int jb) { return s_phys[jb]; }, s_p, ld);
     __syncthreads();
     softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
 
@@ -302,8 +312,8 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
         tau_i[i] = tau < ntok ? tau : -1;
         vw[i] = make_uint4(0, 0, 0, 0);
         if (tau < ntok) {
-          const int gtok = s_idx[tau >> a.log2b] * a.b + (tau & (a.b - 1));
-          vw[i] = ld_stream(V_inst + (size_t)gtok * D + dpart * E);
+          const int ptok = s_phys[tau >> a.log2b] * a.b + (tau & (a.b - 1));
+          vw[i] = ld_stream(V_inst + (size_t)ptok * D + dpart * E);
         }
       }
 #pragma unroll
@@ -377,7 +387,7 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 
 // LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens.
 template <int D, int G> inline size_t sparse_lds_floats(int nblk_cap, int b) {
-  return (size_t)G * nblk_cap * b + kAttnWaves * G * D + (size_t)G * nblk_cap + nblk_cap + 2 * G + nblk_cap;
+  return (size_t)G * nblk_cap * b + kAttnWaves * G * D + (size_t)G * nblk_cap + nblk_cap + 2 * G + 2 * nblk_cap;
 }
 
 }  // namespace

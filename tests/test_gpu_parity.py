@@ -480,3 +480,53 @@ def test_repeated_step_is_bitwise_deterministic():
         for r in results[1:]:
             for a, b in zip(results[0], r):
                 assert torch.equal(a, b)
+
+
+# --------------------------------------------------------------------------------------------- paged K/V
+def _paged_copy(w, run, K, V, dev, seed=3):
+    """Scatters the contiguous caches into one pool of shuffled physical blocks; returns (Kp, Vp, table)."""
+    b, nbc = w.block, run.nb_cap
+    n_phys = w.n_inst * nbc + 5
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    perm = torch.randperm(n_phys, generator=g)[: w.n_inst * nbc].to(dev)
+    table = perm.view(w.n_inst, nbc).to(torch.int32).contiguous()
+    Kp = torch.zeros((n_phys, b, w.head_dim), dtype=K.dtype, device=dev)
+    Vp = torch.zeros_like(Kp)
+    Kp[perm] = K.view(w.n_inst * nbc, b, w.head_dim)
+    Vp[perm] = V.view(w.n_inst * nbc, b, w.head_dim)
+    return Kp, Vp, table, n_phys
+
+
+@pytest.mark.parametrize("kw", [dict(kv_heads=3, t0=3000, budget_tokens=1024), dict(kv_heads=8, batch=130, t0=700),
+                                dict(kv_heads=2, g=1, t0=1500, kv_dtype="f32", head_dim=64)],
+                         ids=["split", "one-wg-per-instance", "f32"])
+def test_paged_kv_equals_contiguous(kw):
+    """A block table that scatters the cache over a pool changes addresses only: same bytes out."""
+    dev = _dev()
+    w = small("paged", hist_len=16, steps=6, calib_every=3, **kw)
+    K, V = kv_cache(w, dev)
+    ref, pag = _run(w, dev), _run(w, dev)
+    Kp, Vp, table, n_phys = _paged_copy(w, pag, K, V, dev)
+    pag.ctx.set_block_table(table, n_phys)
+    H = w.hist_len
+    for j in range(H):
+        q, t = queries(w, j - H, dev), w.t0 - H + 1 + j
+        ref.warmup_calibrate(q, K, t)
+        pag.warmup_calibrate(q, Kp, t)
+    assert torch.equal(ref.hist, pag.hist)
+    for s in range(w.steps):
+        q, t, cal = queries(w, s, dev), w.t_at(s), w.is_calibration_step(s)
+        ref.step(q, K, V, t, calibrate=cal)
+        pag.step(q, Kp, Vp, t, calibrate=cal)
+        torch.cuda.synchronize()
+        assert torch.equal(ref.idx, pag.idx) and torch.equal(ref.out, pag.out) and torch.equal(ref.hist, pag.hist)
+    # and against the oracle, which sees the gathered contiguous cache
+    i = w.n_inst - 1
+    got_idx = pag.idx[i, :int(pag.cnt[i])].cpu().numpy()
+    o, _ = orc.sparse_attention(to_f64(q[i]), to_f64(K[i]), to_f64(V[i]), got_idx, w.block, t)
+    for h in range(w.g):
+        assert_close(pag.out[i, h].cpu().numpy(), o[h], f"paged out head {h}")
+    pag.ctx.set_block_table(None)
+    pag.ctx.sparse_decode(q, K, V, t, pag.idx, pag.cnt, pag.out, pag.row, pag.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ref.out, pag.out)
