@@ -23,8 +23,12 @@ hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred
   const dim3 grid(ninst);
 #define AP_SELECT(KPT) \
   select_topk_kernel<KPT><<<grid, kSelThreads, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local, inst0, idx, cnt)
-  if (n_mid <= 8 * kSelThreads) AP_SELECT(8);
+  if (n_mid <= 8 * kSelThreads) AP_SELECT(8);            // the variants differ only in unrolled trip count
+  else if (n_mid <= 9 * kSelThreads) AP_SELECT(9);
+  else if (n_mid <= 10 * kSelThreads) AP_SELECT(10);
+  else if (n_mid <= 12 * kSelThreads) AP_SELECT(12);
   else if (n_mid <= 16 * kSelThreads) AP_SELECT(16);
+  else if (n_mid <= 24 * kSelThreads) AP_SELECT(24);
   else if (n_mid <= 32 * kSelThreads) AP_SELECT(32);
   else AP_SELECT(0);
 #undef AP_SELECT
