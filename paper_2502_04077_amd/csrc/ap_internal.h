@@ -25,7 +25,7 @@ constexpr int kCalibChunkTokens = 1024;       // tokens per calibration workgrou
 //   b3                         at 10*c1 + 9*c1*c2 + 2*c2
 struct Shape {
   int n_inst, g, d, b, H, R, t_cap, nb_cap, k, n_sink, n_local, c1, c2, kv_dtype;
-  int predictor_mfma; // second conv layer of the incremental predictor on f16 MFMA (8/8 channels only)
+  int predictor_mfma; // incremental predictor on f16 MFMA (8/8 and 16/32 channels)
   int n_split;        // workgroups per instance in sparse decode
   int calib_chunks;   // max workgroups per instance in calibrate
   const int32_t* table;  // device block table of a paged K/V cache [n_inst][nb_cap], or null (caller-owned)
@@ -55,9 +55,22 @@ __host__ __device__ constexpr int predictor_tap(int half, int out, int q) {
 // f16 operand table of the MFMA predictor variant (8/8 channels), built on the host by ap_set_weights:
 // [half 2][K-step 6][lane 64][8 f16], placed kMfmaTableFloatOffset floats into the weight buffer
 // (the fp32 section is 10*8 + 9*64 + 2*8 + 1 = 673 floats; 676 keeps 16-byte alignment).
-// It is followed by the layer-1 table [half 2][lane 64][8 f16]: row m = 8 q + c1, K slot k = 3 * xrow + kw.
+// It is followed by the layer-1 table [half 2][lane 64][8 f16]: row m = 8 q + c1, K slot k = 3 * xrow + kw,
+// scaled by 2^-4.
 constexpr int kMfmaTableFloatOffset = 676;
 constexpr int kMfmaTableHalfs = 2 * 6 * 64 * 8 + 2 * 64 * 8;
+
+// The same for 16/32 channels (fp32 section: 10*16 + 9*16*32 + 2*32 + 1 = 4833 floats):
+// layer 2 [half 2][pair 8][kw 3][lane 64][8 f16], lane (m = lane % 32, h = lane / 32) holding input channels
+// 8h..8h+7 of output channel m for the kernel row that pair (q, o) stands for; then layer 1
+// [half 2][row block 2][lane 64][8 f16], row m = 16 (q % 2) + c1 of row block q / 2, K slot k = 3 * xrow + kw,
+// scaled by 2^-4.  Pairs in table order, with staged rows q and outputs o numbered as the kernel does:
+constexpr int kMfma16TableFloatOffset = 4836;
+constexpr int kMfma16TableHalfs = 2 * 24 * 64 * 8 + 2 * 2 * 64 * 8;
+constexpr int kMfma16PairQ[8] = {0, 1, 1, 1, 2, 2, 3, 3};
+constexpr int kMfma16PairO[8] = {0, 0, 1, 2, 0, 2, 1, 2};
+// Kernel numbering -> the numbering predictor_tap uses (rows and outputs 1, 2 swap in the bottom half).
+__host__ __device__ constexpr int mfma16_phys(int half, int i) { return (half == 1 && (i == 1 || i == 2)) ? 3 - i : i; }
 
 // Launchers.  Each returns hipSuccess or the launch error.
 // Full-tile predictor over columns [col_begin, nb_cur); also writes the interior state if pstate != null.

@@ -78,7 +78,8 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   s.n_inst = c->n_inst; s.g = c->g; s.d = c->head_dim; s.b = c->block; s.H = c->hist_len;
   s.R = c->hist_len + 1; s.t_cap = c->t_cap; s.nb_cap = c->t_cap / c->block; s.k = c->k_blocks;
   s.n_sink = c->n_sink; s.n_local = c->n_local; s.c1 = c->c1; s.c2 = c->c2; s.kv_dtype = c->kv_dtype;
-  s.predictor_mfma = (c->c1 == 8 && c->c2 == 8 && !(c->flags & AP_FLAG_PREDICTOR_FP32)) ? 1 : 0;
+  s.predictor_mfma = (((c->c1 == 8 && c->c2 == 8) || (c->c1 == 16 && c->c2 == 32)) &&
+                      !(c->flags & AP_FLAG_PREDICTOR_FP32)) ? 1 : 0;
   s.n_split = ap::choose_split(s);
   const int chunk_blocks = ap::kCalibChunkTokens / s.b;
   s.calib_chunks = (s.nb_cap + chunk_blocks - 1) / chunk_blocks;
@@ -132,8 +133,9 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   const float* b2 = w2 + 9 * (size_t)c1 * c2;
   const float* w3 = b2 + c2;
   const float* b3 = w3 + c2;
-  const bool mfma_table = (c1 == 8 && c2 == 8);
-  const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + ap::kMfmaTableHalfs / 2 : expect;
+  const bool mfma_table = (c1 == 8 && c2 == 8), mfma16_table = (c1 == 16 && c2 == 32);
+  const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + ap::kMfmaTableHalfs / 2
+                     : mfma16_table ? ap::kMfma16TableFloatOffset + ap::kMfma16TableHalfs / 2 : expect;
   std::vector<float> packed(total, 0.f);
   float* p = packed.data();
   for (int t = 0; t < 9; ++t)
@@ -179,10 +181,42 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
           float v = 0.f;
           if (k < 15) {
             const int kh = k / 3 - base, kw = k % 3;
-            if (kh >= 0 && kh < 3 && kh != zero_kh) v = w1[(c * 3 + kh) * 3 + kw];
+            if (kh >= 0 && kh < 3 && kh != zero_kh) v = w1[(c * 3 + kh) * 3 + kw] * (1.f / 16.f);
           }
           t1[(half * 64 + lane) * 8 + e] = (_Float16)v;
         }
+  }
+  if (mfma16_table) {
+    // A operands of the 16/32-channel kernel (layout and numbering: ap_internal.h).
+    _Float16* t = reinterpret_cast<_Float16*>(packed.data() + ap::kMfma16TableFloatOffset);
+    for (int half = 0; half < 2; ++half)
+      for (int pair = 0; pair < 8; ++pair) {
+        const int kh = ap::predictor_tap(half, ap::mfma16_phys(half, ap::kMfma16PairO[pair]),
+                                         ap::mfma16_phys(half, ap::kMfma16PairQ[pair]));
+        for (int kw = 0; kw < 3; ++kw)
+          for (int lane = 0; lane < 64; ++lane)
+            for (int e = 0; e < 8; ++e) {
+              const int co = lane % 32, ci = 8 * (lane / 32) + e;
+              const float v = kh < 0 ? 0.f : w2[(((size_t)co * c1 + ci) * 3 + kh) * 3 + kw];
+              t[(((half * 8 + pair) * 3 + kw) * 64 + lane) * 8 + e] = (_Float16)v;
+            }
+      }
+    _Float16* t1 = t + 2 * 24 * 64 * 8;
+    for (int half = 0; half < 2; ++half)
+      for (int rb = 0; rb < 2; ++rb)
+        for (int lane = 0; lane < 64; ++lane)
+          for (int e = 0; e < 8; ++e) {
+            const int m = lane % 32, k = 8 * (lane / 32) + e, c = m % 16;
+            const int q = ap::mfma16_phys(half, 2 * rb + m / 16);
+            const int base = (half == 0 && q == 3) ? 0 : q;
+            const int zero_kh = q == 3 ? (half == 0 ? 0 : 2) : -1;
+            float v = 0.f;
+            if (k < 15) {
+              const int kh = k / 3 - base, kw = k % 3;
+              if (kh >= 0 && kh < 3 && kh != zero_kh) v = w1[(c * 3 + kh) * 3 + kw] * (1.f / 16.f);
+            }
+            t1[((half * 2 + rb) * 64 + lane) * 8 + e] = (_Float16)v;
+          }
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->dweights == nullptr &&

@@ -25,6 +25,7 @@
 // which the leaving term needs.  Exact in real arithmetic; in fp32 each step adds two roundings to
 // the state, so callers re-base with the full-tile kernel now and then.
 #include "predict_body.h"
+#include "predict_body16.h"
 
 namespace ap {
 namespace {
@@ -269,6 +270,16 @@ __global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __re
                         advance, pstate, pred, smem);
 }
 
+__global__ __launch_bounds__(256) void predict_inc_mfma16_kernel(const float* __restrict__ hist,
+                                                                 const float* __restrict__ wts_global, int R, int H,
+                                                                 int newest_slot, int nb_cur, int nb_cap, int inst0,
+                                                                 int advance, float* __restrict__ pstate,
+                                                                 float* __restrict__ pred) {
+  extern __shared__ __align__(16) float smem[];
+  predict_inc_mfma16_body(hist, wts_global, R, H, newest_slot, nb_cur, nb_cap, inst0 + blockIdx.y, blockIdx.x,
+                          gridDim.x, advance, pstate, pred, smem);
+}
+
 // Full evaluation of a few columns (the ones whose state is void after the tile has grown by a block):
 // one wave per (instance, column), lanes are time rows.  A lane gathers the 5 x 5 x neighbourhood of its
 // pixel from the ring and evaluates y1 on the 3 x 3 pixels around it channel by channel, feeding y2.
@@ -362,10 +373,19 @@ hipError_t run_inc(const Shape& s, int inst0, int ninst, const float* dweights, 
                    int nb_cur, int advance, float* pstate, float* pred, hipStream_t st) {
   if (C1 == 8 && C2 == 8 && s.predictor_mfma) {
     const size_t lds = sizeof(float) * kPredMfmaLdsFloats;
-    const int tiles = (nb_cur + 125) / 126;
+    const int tiles = (nb_cur + kPmIW - 1) / kPmIW;
     int chunks = (2048 + s.n_inst - 1) / s.n_inst;       // about eight workgroups per CU when instances are few
     if (chunks > tiles) chunks = tiles;
     predict_inc_mfma_kernel<<<dim3(chunks, ninst), 256, lds, st>>>(
+        hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, advance, pstate, pred);
+    return hipGetLastError();
+  }
+  if (C1 == 16 && C2 == 32 && s.predictor_mfma) {
+    const size_t lds = sizeof(float) * kPred16LdsFloats;
+    const int tiles = (nb_cur + kP16IW - 1) / kP16IW;
+    int chunks = (1024 + s.n_inst - 1) / s.n_inst;       // two workgroups fit a CU
+    if (chunks > tiles) chunks = tiles;
+    predict_inc_mfma16_kernel<<<dim3(chunks, ninst), 256, lds, st>>>(
         hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, advance, pstate, pred);
     return hipGetLastError();
   }

@@ -143,7 +143,8 @@ def test_predict_vs_oracle(H, nb, c1, c2, pushed):
 @pytest.mark.parametrize("H,nb0,c1,c2,n_steps,grow_every,fp32", [
     (16, 130, 8, 8, 60, 5, 0), (64, 200, 8, 8, 150, 16, 0), (6, 70, 4, 4, 40, 3, 0), (64, 65, 16, 32, 70, 0, 0),
     (16, 1, 8, 8, 40, 4, 0), (5, 40, 8, 8, 12, 0, 0), (16, 130, 8, 8, 60, 5, 1), (64, 300, 8, 8, 150, 16, 1),
-    (64, 2049, 8, 8, 20, 4, 0),
+    (64, 2049, 8, 8, 20, 4, 0), (64, 300, 16, 32, 80, 8, 0), (16, 122, 16, 32, 40, 5, 1), (6, 123, 16, 32, 24, 2, 0),
+    (64, 2049, 16, 32, 12, 4, 0),
 ])
 def test_predict_incremental_tracks_oracle(H, nb0, c1, c2, n_steps, grow_every, fp32):
     """ADVANCE once per pushed row (no re-base in between), tile growing, ring wrapping: every
