@@ -19,6 +19,7 @@
  * Conventions
  *   - Every pointer named below as "device" is a device pointer owned by the caller, contiguous
  *     in the stated row-major shape and 16-byte aligned.  The library never frees or keeps them.
+ *     (Only ap_prefetch_blocks also takes pinned host memory, and says so.)
  *   - `stream` is a hipStream_t passed as void*; all work is enqueued on it, nothing synchronises.
  *   - Calls return AP_OK or a negative error code; an error found on the host leaves all outputs
  *     untouched.  No call throws.  Only ap_create / ap_set_weights / ap_destroy allocate or free.
@@ -152,7 +153,8 @@ int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, i
                      void* stream);
 
 /* Distribution error calibration (Sec. 3.3): the pooled row of the dense attention of q over all
- * t_cur tokens.  Reads K only and produces no attention output.
+ * t_cur tokens.  Reads K only and produces no attention output.  K may also be pinned (mapped) host
+ * memory, which the kernel then reads over PCIe; pageable host memory is refused with AP_ERR_ARG.
  *   row  device float [n_inst][nb_cap]; entries >= ceil(t_cur/b) are written as 0 */
 int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float* row, void* ws,
                  void* stream);
@@ -169,6 +171,29 @@ int ap_update_history(ap_ctx* ctx, float* hist, int64_t n_pushed, const float* r
 int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* K,
             const void* V, int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred,
             float* pstate, int32_t pred_mode, void* ws, void* stream);
+
+/* K/V cache kept outside the device ("KV Cache Cross-token Prefetching", Sec. 3.4; timeline figure of the
+ * appendix): stage the blocks of one selection.  For every instance and list position p < cnt, block idx[p]
+ * of K_src and V_src is copied into slot inst * k + p of the pools and block_table[inst][idx[p]] = that slot
+ * is recorded, so that after ap_set_block_table(ctx, block_table, n_inst * k) the K/V arguments of
+ * ap_sparse_decode are the pools.  Meant to run on a stream of its own for the NEXT token's selection while
+ * other layers compute; the caller orders it against the calls that produce idx and consume the pools.
+ *   K_src,V_src  [n_inst][t_cap][d] in the kv dtype: device memory, or pinned (mapped) host memory, which
+ *                the kernel then reads over PCIe.  Pageable host memory is refused with AP_ERR_ARG.
+ *   t_avail      tokens whose K/V exist in the source now; rows of later tokens are staged as zeros
+ *                (the token of the step the selection is for is generated after the fetch: ap_append_kv)
+ *   nb_cur       block count the selection was made for (idx entries are clamped into [0, nb_cur))
+ *   pool_K,pool_V device [n_inst * k][b][d] kv dtype; block_table device int32 [n_inst][nb_cap] */
+int ap_prefetch_blocks(ap_ctx* ctx, const void* K_src, const void* V_src, int32_t t_avail, int32_t nb_cur,
+                       const int32_t* idx, const int32_t* cnt, void* pool_K, void* pool_V,
+                       int32_t* block_table, void* stream);
+
+/* Appends the new token's K/V row (token index t_pos, so t_cur = t_pos + 1 in the decode call that follows) to
+ * the staged copy of its block.  Nothing is written for an instance whose selection does not end with block
+ * t_pos / b (with n_local >= 1 it always does).
+ *   k_new,v_new  device [n_inst][d] kv dtype */
+int ap_append_kv(ap_ctx* ctx, const void* k_new, const void* v_new, int32_t t_pos, const int32_t* idx,
+                 const int32_t* cnt, void* pool_K, void* pool_V, void* stream);
 
 /* Measurement aids (no part of Algorithm 1): a streaming read of `bytes` bytes (multiple of 16) of
  * device memory with 16-byte loads per lane, and a plain copy.  They give the read bandwidth the

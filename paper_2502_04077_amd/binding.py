@@ -17,11 +17,12 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libattnpre
 AP_F32, AP_BF16 = 0, 1
 AP_PRED_REBASE, AP_PRED_ADVANCE, AP_PRED_HOLD = 0, 1, 2
 AP_FLAG_PREDICTOR_FP32 = 1
+AP_OK, AP_ERR_ARG, AP_ERR_ALIGN, AP_ERR_RANGE, AP_ERR_HIP, AP_ERR_UNSUPPORTED, AP_ERR_STATE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_set_block_table",
     "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
-    "ap_stream_read", "ap_stream_copy", "ap_strerror",
+    "ap_prefetch_blocks", "ap_append_kv", "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
 
 
@@ -68,6 +69,8 @@ def load_library() -> C.CDLL:
     lib.ap_calibrate.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.ap_update_history.argtypes = [vp, vp, i64, vp, vp]
     lib.ap_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.ap_prefetch_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ap_append_kv.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.ap_stream_read.argtypes = [vp, sz, vp, i32, vp]
     lib.ap_stream_copy.argtypes = [vp, sz, vp, i32, vp]
     lib.ap_strerror.argtypes = [C.c_int]
@@ -87,6 +90,13 @@ def _check(rc: int) -> None:
 def _ptr(t: torch.Tensor) -> int:
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _rptr(t: torch.Tensor) -> int:
+    """A tensor a kernel may read: device memory, or pinned (device-mapped) host memory."""
+    if not (t.is_cuda or t.is_pinned()) or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor or pinned host tensor")
     return t.data_ptr()
 
 
@@ -162,7 +172,15 @@ class Context:
                                           _ptr(out), _ptr(row), _ptr(ws), _stream()))
 
     def calibrate(self, q, K, t_cur, row, ws) -> None:
-        _check(self._lib.ap_calibrate(self._h, _ptr(q), _ptr(K), t_cur, _ptr(row), _ptr(ws), _stream()))
+        _check(self._lib.ap_calibrate(self._h, _ptr(q), _rptr(K), t_cur, _ptr(row), _ptr(ws), _stream()))
+
+    def prefetch_blocks(self, K_src, V_src, t_avail, nb_cur, idx, cnt, pool_K, pool_V, table) -> None:
+        _check(self._lib.ap_prefetch_blocks(self._h, _rptr(K_src), _rptr(V_src), t_avail, nb_cur, _ptr(idx), _ptr(cnt),
+                                            _ptr(pool_K), _ptr(pool_V), _ptr(table), _stream()))
+
+    def append_kv(self, k_new, v_new, t_pos, idx, cnt, pool_K, pool_V) -> None:
+        _check(self._lib.ap_append_kv(self._h, _ptr(k_new), _ptr(v_new), t_pos, _ptr(idx), _ptr(cnt), _ptr(pool_K),
+                                      _ptr(pool_V), _stream()))
 
     def update_history(self, hist, n_pushed, row) -> None:
         _check(self._lib.ap_update_history(self._h, _ptr(hist), n_pushed, _ptr(row), _stream()))

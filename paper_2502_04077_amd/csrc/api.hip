@@ -305,11 +305,24 @@ int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, i
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+// A pointer a kernel may read: device memory, or host memory that is pinned and mapped.  Pageable
+// host memory would fault the GPU, so it is refused here.
+static int check_device_readable(const void* p) {
+  hipPointerAttribute_t a;
+  if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+    (void)hipGetLastError();
+    return AP_ERR_ARG;
+  }
+  const bool ok = a.type == hipMemoryTypeHost || a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged;
+  return ok ? AP_OK : AP_ERR_ARG;
+}
+
 int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float* row, void* ws, void* stream) {
   if (ctx == nullptr) return AP_ERR_ARG;
   AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(row); AP_REQUIRE_PTR(ws);
   const Shape& s = ctx->s;
   if (t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
+  if (check_device_readable(K) != AP_OK) return AP_ERR_ARG;
   hipError_t e = ap::launch_calibrate(s, q, K, t_cur, row, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
@@ -346,6 +359,32 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
                                static_cast<float*>(ws), st) != hipSuccess)
     return AP_ERR_HIP;
   return AP_OK;
+}
+
+int ap_prefetch_blocks(ap_ctx* ctx, const void* K_src, const void* V_src, int32_t t_avail, int32_t nb_cur,
+                       const int32_t* idx, const int32_t* cnt, void* pool_K, void* pool_V, int32_t* block_table,
+                       void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(K_src); AP_REQUIRE_PTR(V_src); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V); AP_REQUIRE_PTR(block_table);
+  const Shape& s = ctx->s;
+  if (nb_cur < 1 || nb_cur > s.nb_cap || t_avail < 0 || t_avail > s.t_cap) return AP_ERR_RANGE;
+  if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
+  hipError_t e = ap::launch_gather_blocks(s, K_src, V_src, t_avail, nb_cur, idx, cnt, pool_K, pool_V, block_table,
+                                          static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+int ap_append_kv(ap_ctx* ctx, const void* k_new, const void* v_new, int32_t t_pos, const int32_t* idx,
+                 const int32_t* cnt, void* pool_K, void* pool_V, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(k_new); AP_REQUIRE_PTR(v_new); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V);
+  const Shape& s = ctx->s;
+  if (t_pos < 0 || t_pos >= s.t_cap) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_append_row(s, k_new, v_new, t_pos, idx, cnt, pool_K, pool_V,
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
 int ap_stream_read(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream) {
