@@ -83,6 +83,97 @@ def cpu_baseline(w, run, K, V, budget_s=20.0, max_inst=16):
     }
 
 
+def main_offload(args):
+    """Decode with the K/V cache in pinned host memory: per layer, the next token's selected blocks are gathered
+    over PCIe on a second stream while the other layers compute.  Reported beside it: the time a dense-attention
+    offload scheme needs just to move the whole cache to the device once per token (its lower bound)."""
+    import torch
+    from paper_2502_04077_amd.offload import OffloadRun
+    from workloads import CONFIGS, kv_cache, predictor_weights, queries
+
+    steps = min(args.steps, 128)
+    total_steps = args.warmup + steps
+    w = CONFIGS["cfg1"].with_(name="cfg1x32-offload" + ("-planted" if args.planted else ""), layers=32,
+                              steps=total_steps, planted=args.planted)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, V = kv_cache(w, dev)
+    K_host = torch.empty(K.shape, dtype=K.dtype, pin_memory=True)
+    V_host = torch.empty(V.shape, dtype=V.dtype, pin_memory=True)
+    K_host.copy_(K)
+    V_host.copy_(V)
+    first = w.t_at(0) - 1                                  # index of the first decoded token
+    k_new = K[:, first:first + total_steps, :].transpose(0, 1).contiguous()   # [step][n_inst][d]
+    v_new = V[:, first:first + total_steps, :].transpose(0, 1).contiguous()
+    del K, V
+    torch.cuda.empty_cache()
+    run = OffloadRun(w, K_host, V_host, dev)
+    run.set_weights(predictor_weights(w))
+    H = w.hist_len
+    for j in range(H):
+        run.warmup_calibrate(queries(w, j - H, dev), w.t0 - H + 1 + j)
+    qs = [queries(w, s, dev) for s in range(total_steps)]
+    run.start(w.t_at(0))
+    torch.cuda.synchronize()
+
+    def one_step(s, calib=None):
+        run.step(qs[s], k_new[s], v_new[s], w.t_at(s), calibrate=w.is_calibration_step(s) if calib is None else calib)
+
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    fetched0 = run.blocks_fetched()
+    t0 = time.perf_counter()
+    for s in range(args.warmup, total_steps):
+        one_step(s)
+    issued = time.perf_counter() - t0                      # host time to enqueue the steps
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_calib = sum(1 for s in range(args.warmup, total_steps) if w.is_calibration_step(s))
+    run.finish()
+    ms_per_step = elapsed * 1e3 / steps
+    fetched = run.blocks_fetched() - fetched0              # blocks that actually crossed the link
+
+    # The dense alternative must at least bring every K and V row to the device once per token.
+    esize = K_host.element_size()
+    t_mid = w.t_at(args.warmup + steps // 2)
+    layer_rows = run.ipl
+    stage = torch.empty((layer_rows, w.t_cap, w.head_dim), dtype=K_host.dtype, device=dev)
+    for rep in range(2):
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for l in range(w.layers):
+            stage.copy_(K_host[l * layer_rows:(l + 1) * layer_rows], non_blocking=True)
+            stage.copy_(V_host[l * layer_rows:(l + 1) * layer_rows], non_blocking=True)
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - c0) * 1e3
+    dense_bytes = 2 * w.n_inst * w.t_cap * w.head_dim * esize
+    block_bytes = 2 * w.block * w.head_dim * esize         # K and V
+    selected_bytes = w.n_inst * w.k_blocks * block_bytes   # per step, were every selected block fetched
+    staged_bytes = fetched * block_bytes / steps           # per step, fetched in fact (blocks that stay selected are kept)
+    calib_bytes = w.n_inst * t_mid * w.head_dim * esize
+    out = {
+        "metric": "decode steps/s with the K/V cache in host memory (cross-token prefetch of the selected blocks)",
+        "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "host_enqueue_ms_per_step": issued * 1e3 / steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "instances": w.n_inst, "layers": w.layers, "batch": w.batch,
+                   "kv_heads": w.kv_heads, "q_per_kv": w.g, "head_dim": w.head_dim, "context": w.t0, "block": w.block,
+                   "history": w.hist_len, "budget_tokens": w.budget_tokens, "predictor_channels": [w.c1, w.c2],
+                   "calibration_every": w.calib_every, "calibration_steps_in_timed_region": n_calib,
+                   "kv_cache": "pinned host memory", "host_cache_GB": dense_bytes / 1e9},
+        "pcie": {"selected_MB_per_step": selected_bytes / 1e6, "fetched_MB_per_step": staged_bytes / 1e6,
+                 "fetched_fraction_of_selected": staged_bytes / selected_bytes,
+                 "calibration_MB_per_step_amortised": calib_bytes * n_calib / steps / 1e6,
+                 "achieved_GBs": (staged_bytes * steps + calib_bytes * n_calib) / elapsed / 1e9},
+        "dense_offload_transfer": {"ms_per_token": dense_ms, "GBs": dense_bytes / dense_ms / 1e6,
+                                   "what": "hipMemcpyAsync of the whole K and V cache to the device, no compute"},
+        "speedup_vs_dense_transfer": dense_ms / ms_per_step,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap_ = argparse.ArgumentParser()
     ap_.add_argument("--gpus", type=int, default=1)
@@ -91,11 +182,20 @@ def main():
     ap_.add_argument("--workload", default="cfg2", help="cfg0..cfg4 (default: cfg2, the 32-layer batch-8 32K case)")
     ap_.add_argument("--no-cpu-baseline", action="store_true")
     ap_.add_argument("--no-breakdown", action="store_true")
+    ap_.add_argument("--offload", action="store_true",
+                     help="K/V in pinned host memory with cross-token prefetching (Sec. 3.4); one 8B-shaped model, "
+                          "batch 1, 32 layers, 32K context; prints its own JSON line")
+    ap_.add_argument("--planted", action="store_true",
+                     help="with --offload: keys and queries with the planted sink / stripe / local / slash structure of "
+                          "cfg4 instead of plain Gaussian ones")
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (instances are independent, "
               "sharding is described in DESIGN.md but not built).", file=sys.stderr)
         sys.exit(2)
+
+    if args.offload:
+        return main_offload(args)
 
     import torch
     from paper_2502_04077_amd.runner import DecodeRun

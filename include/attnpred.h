@@ -22,7 +22,8 @@
  *     (Only ap_prefetch_blocks also takes pinned host memory, and says so.)
  *   - `stream` is a hipStream_t passed as void*; all work is enqueued on it, nothing synchronises.
  *   - Calls return AP_OK or a negative error code; an error found on the host leaves all outputs
- *     untouched.  No call throws.  Only ap_create / ap_set_weights / ap_destroy allocate or free.
+ *     untouched.  No call throws.  Only ap_create / ap_set_weights / ap_destroy allocate or free
+ *     (ap_offload_begin creates two events on its first call).
  *   - All instances share one length t_cur per call.
  *   - Inputs must be finite; NaN scores give an unspecified (but in-range, duplicate-free) selection.
  */
@@ -173,27 +174,59 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
             float* pstate, int32_t pred_mode, void* ws, void* stream);
 
 /* K/V cache kept outside the device ("KV Cache Cross-token Prefetching", Sec. 3.4; timeline figure of the
- * appendix): stage the blocks of one selection.  For every instance and list position p < cnt, block idx[p]
- * of K_src and V_src is copied into slot inst * k + p of the pools and block_table[inst][idx[p]] = that slot
- * is recorded, so that after ap_set_block_table(ctx, block_table, n_inst * k) the K/V arguments of
- * ap_sparse_decode are the pools.  Meant to run on a stream of its own for the NEXT token's selection while
- * other layers compute; the caller orders it against the calls that produce idx and consume the pools.
+ * appendix): stage the blocks of one selection in a device pool of k slots per instance.  The pool works as
+ * a cache: a selected block that is already staged keeps its slot; a block that is new to the selection is
+ * copied from K_src / V_src into a slot whose block has left the selection.  block_table[inst][block] receives
+ * the slot (inst * k + slot index) of every selected block, so that after
+ * ap_set_block_table(ctx, block_table, n_inst * k) the K/V arguments of ap_sparse_decode are the pools.
+ * Meant to run on a stream of its own for the NEXT token's selection while other layers compute; the caller
+ * orders it against the calls that produce idx and consume the pools.
  *   K_src,V_src  [n_inst][t_cap][d] in the kv dtype: device memory, or pinned (mapped) host memory, which
  *                the kernel then reads over PCIe.  Pageable host memory is refused with AP_ERR_ARG.
  *   t_avail      tokens whose K/V exist in the source now; rows of later tokens are staged as zeros
  *                (the token of the step the selection is for is generated after the fetch: ap_append_kv)
  *   nb_cur       block count the selection was made for (idx entries are clamped into [0, nb_cur))
- *   pool_K,pool_V device [n_inst * k][b][d] kv dtype; block_table device int32 [n_inst][nb_cap] */
+ *   pool_K,pool_V device [n_inst * k][b][d] kv dtype; block_table device int32 [n_inst][nb_cap]
+ *   state        device int32, ap_prefetch_state_bytes(ctx) bytes, zero-filled before the first call and
+ *                then only touched by these calls: which block each slot holds.  Zero-filling it again
+ *                empties the cache (every selected block is then fetched).  Word 3k+1 of each instance's
+ *                3k+4 words counts the blocks fetched since the state was zeroed.
+ * k <= 256. */
+size_t ap_prefetch_state_bytes(const ap_ctx* ctx);
 int ap_prefetch_blocks(ap_ctx* ctx, const void* K_src, const void* V_src, int32_t t_avail, int32_t nb_cur,
                        const int32_t* idx, const int32_t* cnt, void* pool_K, void* pool_V,
-                       int32_t* block_table, void* stream);
+                       int32_t* block_table, int32_t* state, void* stream);
 
 /* Appends the new token's K/V row (token index t_pos, so t_cur = t_pos + 1 in the decode call that follows) to
- * the staged copy of its block.  Nothing is written for an instance whose selection does not end with block
- * t_pos / b (with n_local >= 1 it always does).
+ * the staged copy of block t_pos / b.  Nothing is written for an instance that has not staged that block (with
+ * n_local >= 1 it always has).  The full cache itself is not updated: writing the row back to it is the
+ * caller's business.
  *   k_new,v_new  device [n_inst][d] kv dtype */
-int ap_append_kv(ap_ctx* ctx, const void* k_new, const void* v_new, int32_t t_pos, const int32_t* idx,
-                 const int32_t* cnt, void* pool_K, void* pool_V, void* stream);
+int ap_append_kv(ap_ctx* ctx, const void* k_new, const void* v_new, int32_t t_pos, const int32_t* block_table,
+                 const int32_t* state, void* pool_K, void* pool_V, void* stream);
+
+/* One layer's decode step in the cross-token prefetching schedule (Sec. 3.4; timeline figure of the appendix),
+ * enqueued in one call so that a model with many layers is not bound by the host's launch rate:
+ *   compute_stream  wait until this context's staged blocks have arrived -> ap_append_kv -> ap_sparse_decode over
+ *                   the pools (pooled row written into ring slot n_pushed % R) -> if `calibrate`: ap_calibrate
+ *                   from K_src and ap_update_history over that slot -> predict (with n_pushed + 1 rows, pred_mode
+ *                   = AP_PRED_ADVANCE or AP_PRED_REBASE) and select for context length t_cur + 1
+ *   copy_stream     after that selection: ap_prefetch_blocks with t_avail = t_cur
+ * idx / cnt hold this token's selection on entry and the next token's on return; out is this token's output.
+ * ap_offload_begin makes the first selection (full-tile predictor) and stages it with t_avail = t_first - 1;
+ * it must precede the first ap_offload_step.  Both streams must be distinct from each other only if overlap
+ * is wanted; the context owns the two events that order them.  Nothing is prepared when t_cur = t_cap.
+ * Arguments as in the single calls; the context's own block-table setting is neither used nor changed.
+ * Requires n_local >= 1 (the newest block is then always staged). */
+int ap_offload_begin(ap_ctx* ctx, const float* hist, int64_t n_pushed, const void* K_src, const void* V_src,
+                     int32_t t_first, int32_t* idx, int32_t* cnt, float* pred, float* pstate, void* pool_K,
+                     void* pool_V, int32_t* block_table, int32_t* state, void* ws, void* compute_stream,
+                     void* copy_stream);
+int ap_offload_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* k_new,
+                    const void* v_new, const void* K_src, const void* V_src, int32_t t_cur, int32_t calibrate,
+                    float* out, int32_t* idx, int32_t* cnt, float* pred, float* pstate, int32_t pred_mode,
+                    void* pool_K, void* pool_V, int32_t* block_table, int32_t* state, float* row, void* ws,
+                    void* compute_stream, void* copy_stream);
 
 /* Measurement aids (no part of Algorithm 1): a streaming read of `bytes` bytes (multiple of 16) of
  * device memory with 16-byte loads per lane, and a plain copy.  They give the read bandwidth the

@@ -22,7 +22,7 @@ AP_OK, AP_ERR_ARG, AP_ERR_ALIGN, AP_ERR_RANGE, AP_ERR_HIP, AP_ERR_UNSUPPORTED, A
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_set_block_table",
     "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
-    "ap_prefetch_blocks", "ap_append_kv", "ap_stream_read", "ap_stream_copy", "ap_strerror",
+    "ap_prefetch_state_bytes", "ap_prefetch_blocks", "ap_append_kv", "ap_offload_begin", "ap_offload_step", "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
 
 
@@ -69,14 +69,19 @@ def load_library() -> C.CDLL:
     lib.ap_calibrate.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.ap_update_history.argtypes = [vp, vp, i64, vp, vp]
     lib.ap_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
-    lib.ap_prefetch_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.ap_prefetch_state_bytes.argtypes = [vp]
+    lib.ap_prefetch_state_bytes.restype = sz
+    lib.ap_prefetch_blocks.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.ap_append_kv.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.ap_offload_begin.argtypes = [vp, vp, i64, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.ap_offload_step.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp,
+                                    vp, vp, vp, vp]
     lib.ap_stream_read.argtypes = [vp, sz, vp, i32, vp]
     lib.ap_stream_copy.argtypes = [vp, sz, vp, i32, vp]
     lib.ap_strerror.argtypes = [C.c_int]
     lib.ap_strerror.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_strerror"):
+        if name not in ("ap_workspace_bytes", "ap_prefetch_state_bytes", "ap_hist_slots", "ap_nb_cap", "ap_strerror"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -174,12 +179,28 @@ class Context:
     def calibrate(self, q, K, t_cur, row, ws) -> None:
         _check(self._lib.ap_calibrate(self._h, _ptr(q), _rptr(K), t_cur, _ptr(row), _ptr(ws), _stream()))
 
-    def prefetch_blocks(self, K_src, V_src, t_avail, nb_cur, idx, cnt, pool_K, pool_V, table) -> None:
-        _check(self._lib.ap_prefetch_blocks(self._h, _rptr(K_src), _rptr(V_src), t_avail, nb_cur, _ptr(idx), _ptr(cnt),
-                                            _ptr(pool_K), _ptr(pool_V), _ptr(table), _stream()))
+    def prefetch_state_bytes(self) -> int:
+        return int(self._lib.ap_prefetch_state_bytes(self._h))
 
-    def append_kv(self, k_new, v_new, t_pos, idx, cnt, pool_K, pool_V) -> None:
-        _check(self._lib.ap_append_kv(self._h, _ptr(k_new), _ptr(v_new), t_pos, _ptr(idx), _ptr(cnt), _ptr(pool_K),
+    def prefetch_blocks(self, K_src, V_src, t_avail, nb_cur, idx, cnt, pool_K, pool_V, table, state) -> None:
+        _check(self._lib.ap_prefetch_blocks(self._h, _rptr(K_src), _rptr(V_src), t_avail, nb_cur, _ptr(idx), _ptr(cnt),
+                                            _ptr(pool_K), _ptr(pool_V), _ptr(table), _ptr(state), _stream()))
+
+    def offload_begin(self, hist, n_pushed, K_src, V_src, t_first, idx, cnt, pred, pstate, pool_K, pool_V, table, state,
+                      ws, copy_stream) -> None:
+        _check(self._lib.ap_offload_begin(self._h, _ptr(hist), n_pushed, _rptr(K_src), _rptr(V_src), t_first, _ptr(idx),
+                                          _ptr(cnt), _ptr(pred), _ptr(pstate), _ptr(pool_K), _ptr(pool_V), _ptr(table),
+                                          _ptr(state), _ptr(ws), _stream(), copy_stream.cuda_stream))
+
+    def offload_step(self, hist, n_pushed, q, k_new, v_new, K_src, V_src, t_cur, calibrate, out, idx, cnt, pred, pstate,
+                     pred_mode, pool_K, pool_V, table, state, row, ws, copy_stream) -> None:
+        _check(self._lib.ap_offload_step(self._h, _ptr(hist), n_pushed, _ptr(q), _ptr(k_new), _ptr(v_new), _rptr(K_src),
+                                         _rptr(V_src), t_cur, int(bool(calibrate)), _ptr(out), _ptr(idx), _ptr(cnt),
+                                         _ptr(pred), _ptr(pstate), pred_mode, _ptr(pool_K), _ptr(pool_V), _ptr(table),
+                                         _ptr(state), _ptr(row), _ptr(ws), _stream(), copy_stream.cuda_stream))
+
+    def append_kv(self, k_new, v_new, t_pos, table, state, pool_K, pool_V) -> None:
+        _check(self._lib.ap_append_kv(self._h, _ptr(k_new), _ptr(v_new), t_pos, _ptr(table), _ptr(state), _ptr(pool_K),
                                       _ptr(pool_V), _stream()))
 
     def update_history(self, hist, n_pushed, row) -> None:

@@ -93,14 +93,16 @@ hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void
                                 size_t row_stride, float* ws, hipStream_t st);
 hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row,
                             float* ws, hipStream_t st);
-// Copies the selected blocks of the full cache (pinned host or device memory) into pool slots inst * k + list
-// position and records the slots in `table`; rows of tokens >= t_avail are zero-filled.
+// Stages the selected blocks of the full cache (pinned host or device memory) that the pool does not hold yet,
+// into slots freed by blocks that left the selection; records slots in `table` and in `state`
+// (int32 [n_inst][prefetch_state_stride]); rows of tokens >= t_avail are zero-filled.
+int prefetch_state_stride(const Shape& s);
 hipError_t launch_gather_blocks(const Shape& s, const void* K_src, const void* V_src, int t_avail, int nb_cur,
                                 const int32_t* idx, const int32_t* cnt, void* pool_K, void* pool_V, int32_t* table,
-                                hipStream_t st);
-// Writes the K/V row of token t_pos into the staged copy of its block (if that block is selected).
-hipError_t launch_append_row(const Shape& s, const void* k_new, const void* v_new, int t_pos, const int32_t* idx,
-                             const int32_t* cnt, void* pool_K, void* pool_V, hipStream_t st);
+                                int32_t* state, hipStream_t st);
+// Writes the K/V row of token t_pos into the staged copy of its block (if that block is staged).
+hipError_t launch_append_row(const Shape& s, const void* k_new, const void* v_new, int t_pos, const int32_t* table,
+                             const int32_t* state, void* pool_K, void* pool_V, hipStream_t st);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int n_wg, hipStream_t st);
 hipError_t launch_stream_copy(const void* src, size_t bytes, void* dst, int n_wg, hipStream_t st);
 hipError_t launch_push_row(const Shape& s, float* hist, int slot, const float* row, hipStream_t st);

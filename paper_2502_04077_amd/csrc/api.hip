@@ -8,6 +8,9 @@ struct ap_ctx {
   ap::Shape s;
   float* dweights;      // device copy of the re-packed predictor weights, owned
   bool have_weights;
+  // ap_offload_*: "selection for the next token is written" / "its blocks are staged"; created on first use, owned
+  hipEvent_t ev_selected, ev_staged;
+  bool have_events;
 };
 
 namespace ap {
@@ -88,6 +91,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   s.n_phys = 0;
   ctx->dweights = nullptr;
   ctx->have_weights = false;
+  ctx->have_events = false;
   *out = ctx;
   return AP_OK;
 }
@@ -96,6 +100,10 @@ int ap_destroy(ap_ctx* ctx) {
   if (ctx == nullptr) return AP_ERR_ARG;
   int rc = AP_OK;
   if (ctx->dweights != nullptr && hipFree(ctx->dweights) != hipSuccess) rc = AP_ERR_HIP;
+  if (ctx->have_events) {
+    if (hipEventDestroy(ctx->ev_selected) != hipSuccess) rc = AP_ERR_HIP;
+    if (hipEventDestroy(ctx->ev_staged) != hipSuccess) rc = AP_ERR_HIP;
+  }
   delete ctx;
   return rc;
 }
@@ -361,30 +369,124 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
   return AP_OK;
 }
 
+size_t ap_prefetch_state_bytes(const ap_ctx* ctx) {
+  if (ctx == nullptr) return 0;
+  return (size_t)ctx->s.n_inst * ap::prefetch_state_stride(ctx->s) * sizeof(int32_t);
+}
+
 int ap_prefetch_blocks(ap_ctx* ctx, const void* K_src, const void* V_src, int32_t t_avail, int32_t nb_cur,
                        const int32_t* idx, const int32_t* cnt, void* pool_K, void* pool_V, int32_t* block_table,
-                       void* stream) {
+                       int32_t* state, void* stream) {
   if (ctx == nullptr) return AP_ERR_ARG;
   AP_REQUIRE_PTR(K_src); AP_REQUIRE_PTR(V_src); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
-  AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V); AP_REQUIRE_PTR(block_table);
+  AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V); AP_REQUIRE_PTR(block_table); AP_REQUIRE_PTR(state);
   const Shape& s = ctx->s;
+  if (s.k > 256) return AP_ERR_UNSUPPORTED;
   if (nb_cur < 1 || nb_cur > s.nb_cap || t_avail < 0 || t_avail > s.t_cap) return AP_ERR_RANGE;
   if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
   hipError_t e = ap::launch_gather_blocks(s, K_src, V_src, t_avail, nb_cur, idx, cnt, pool_K, pool_V, block_table,
-                                          static_cast<hipStream_t>(stream));
+                                          state, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
-int ap_append_kv(ap_ctx* ctx, const void* k_new, const void* v_new, int32_t t_pos, const int32_t* idx,
-                 const int32_t* cnt, void* pool_K, void* pool_V, void* stream) {
+int ap_append_kv(ap_ctx* ctx, const void* k_new, const void* v_new, int32_t t_pos, const int32_t* block_table,
+                 const int32_t* state, void* pool_K, void* pool_V, void* stream) {
   if (ctx == nullptr) return AP_ERR_ARG;
-  AP_REQUIRE_PTR(k_new); AP_REQUIRE_PTR(v_new); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  AP_REQUIRE_PTR(k_new); AP_REQUIRE_PTR(v_new); AP_REQUIRE_PTR(block_table); AP_REQUIRE_PTR(state);
   AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V);
   const Shape& s = ctx->s;
   if (t_pos < 0 || t_pos >= s.t_cap) return AP_ERR_RANGE;
-  hipError_t e = ap::launch_append_row(s, k_new, v_new, t_pos, idx, cnt, pool_K, pool_V,
+  hipError_t e = ap::launch_append_row(s, k_new, v_new, t_pos, block_table, state, pool_K, pool_V,
                                        static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+static int offload_events(ap_ctx* ctx) {
+  if (ctx->have_events) return AP_OK;
+  if (hipEventCreateWithFlags(&ctx->ev_selected, hipEventDisableTiming) != hipSuccess) return AP_ERR_HIP;
+  if (hipEventCreateWithFlags(&ctx->ev_staged, hipEventDisableTiming) != hipSuccess) {
+    (void)hipEventDestroy(ctx->ev_selected);
+    return AP_ERR_HIP;
+  }
+  ctx->have_events = true;
+  return AP_OK;
+}
+
+// Predict + select for context length t_next on `cs`, then the gather of that selection on `ps`.
+static int offload_select_and_fetch(ap_ctx* ctx, const float* hist, int64_t n_pushed, const void* K_src,
+                                    const void* V_src, int t_next, int t_avail, int mode, int32_t* idx, int32_t* cnt,
+                                    float* pred, float* pstate, void* pool_K, void* pool_V, int32_t* table,
+                                    int32_t* state, hipStream_t cs, hipStream_t ps) {
+  const Shape& s = ctx->s;
+  const int nb_next = (t_next + s.b - 1) / s.b;
+  const int nb_prev = t_next > 1 ? (t_next - 1 + s.b - 1) / s.b : 1;
+  int rc = run_predictor(ctx, hist, n_pushed, nb_next, nb_prev, mode, pstate, pred, cs);
+  if (rc != AP_OK) return rc;
+  if (ap::launch_select(s, 0, s.n_inst, pred, nb_next, idx, cnt, cs) != hipSuccess) return AP_ERR_HIP;
+  if (hipEventRecord(ctx->ev_selected, cs) != hipSuccess) return AP_ERR_HIP;
+  if (hipStreamWaitEvent(ps, ctx->ev_selected, 0) != hipSuccess) return AP_ERR_HIP;
+  if (ap::launch_gather_blocks(s, K_src, V_src, t_avail, nb_next, idx, cnt, pool_K, pool_V, table, state, ps) !=
+      hipSuccess)
+    return AP_ERR_HIP;
+  if (hipEventRecord(ctx->ev_staged, ps) != hipSuccess) return AP_ERR_HIP;
+  return AP_OK;
+}
+
+int ap_offload_begin(ap_ctx* ctx, const float* hist, int64_t n_pushed, const void* K_src, const void* V_src,
+                     int32_t t_first, int32_t* idx, int32_t* cnt, float* pred, float* pstate, void* pool_K,
+                     void* pool_V, int32_t* block_table, int32_t* state, void* ws, void* compute_stream,
+                     void* copy_stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(K_src); AP_REQUIRE_PTR(V_src); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  AP_REQUIRE_PTR(pred); AP_REQUIRE_PTR(pstate); AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V);
+  AP_REQUIRE_PTR(block_table); AP_REQUIRE_PTR(state); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (!ctx->have_weights) return AP_ERR_STATE;
+  if (s.n_local < 1 || s.k > 256) return AP_ERR_UNSUPPORTED;
+  if (n_pushed < 0 || t_first < 1 || t_first > s.t_cap) return AP_ERR_RANGE;
+  if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
+  int rc = offload_events(ctx);
+  if (rc != AP_OK) return rc;
+  return offload_select_and_fetch(ctx, hist, n_pushed, K_src, V_src, t_first, t_first - 1, AP_PRED_REBASE, idx, cnt, pred,
+                                  pstate, pool_K, pool_V, block_table, state, static_cast<hipStream_t>(compute_stream),
+                                  static_cast<hipStream_t>(copy_stream));
+}
+
+int ap_offload_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* k_new, const void* v_new,
+                    const void* K_src, const void* V_src, int32_t t_cur, int32_t calibrate, float* out, int32_t* idx,
+                    int32_t* cnt, float* pred, float* pstate, int32_t pred_mode, void* pool_K, void* pool_V,
+                    int32_t* block_table, int32_t* state, float* row, void* ws, void* compute_stream,
+                    void* copy_stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(hist); AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(k_new); AP_REQUIRE_PTR(v_new); AP_REQUIRE_PTR(K_src);
+  AP_REQUIRE_PTR(V_src); AP_REQUIRE_PTR(out); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt); AP_REQUIRE_PTR(pred);
+  AP_REQUIRE_PTR(pstate); AP_REQUIRE_PTR(pool_K); AP_REQUIRE_PTR(pool_V); AP_REQUIRE_PTR(block_table);
+  AP_REQUIRE_PTR(state); AP_REQUIRE_PTR(row); AP_REQUIRE_PTR(ws);
+  const Shape& s = ctx->s;
+  if (!ctx->have_weights || !ctx->have_events) return AP_ERR_STATE;      // ap_offload_begin comes first
+  if (pred_mode != AP_PRED_REBASE && pred_mode != AP_PRED_ADVANCE) return AP_ERR_ARG;
+  if (n_pushed < 0 || t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
+  if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream), ps = static_cast<hipStream_t>(copy_stream);
+  if (hipStreamWaitEvent(cs, ctx->ev_staged, 0) != hipSuccess) return AP_ERR_HIP;
+  if (ap::launch_append_row(s, k_new, v_new, t_cur - 1, block_table, state, pool_K, pool_V, cs) != hipSuccess)
+    return AP_ERR_HIP;
+  Shape paged = s;                       // the staged pools are a paged cache of n_inst * k blocks
+  paged.table = block_table;
+  paged.n_phys = s.n_inst * s.k;
+  float* slot_row = hist + (size_t)(n_pushed % s.R) * s.nb_cap;
+  if (ap::launch_sparse_decode(paged, 0, s.n_inst, q, pool_K, pool_V, t_cur, idx, cnt, out, slot_row,
+                               (size_t)s.R * s.nb_cap, static_cast<float*>(ws), cs) != hipSuccess)
+    return AP_ERR_HIP;
+  if (calibrate) {
+    Shape flat = s;                      // the dense pass reads the full cache where it lives
+    flat.table = nullptr;
+    if (ap::launch_calibrate(flat, q, K_src, t_cur, row, static_cast<float*>(ws), cs) != hipSuccess) return AP_ERR_HIP;
+    if (ap::launch_push_row(s, hist, (int)(n_pushed % s.R), row, cs) != hipSuccess) return AP_ERR_HIP;
+  }
+  if (t_cur + 1 > s.t_cap) return AP_OK; // the cache is full: no next token to prepare
+  return offload_select_and_fetch(ctx, hist, n_pushed + 1, K_src, V_src, t_cur + 1, t_cur, pred_mode, idx, cnt, pred,
+                                  pstate, pool_K, pool_V, block_table, state, cs, ps);
 }
 
 int ap_stream_read(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream) {

@@ -24,8 +24,9 @@ class _Layer:
 
 
 class OffloadRun:
-    def __init__(self, w, K_host, V_host, device="cuda:0", rebase_every=512, flags=0):
-        """w: Workload; K_host, V_host: pinned host tensors [n_inst][t_cap][d] (instances layer-major)."""
+    def __init__(self, w, K_host, V_host, device="cuda:0", rebase_every=512, flags=0, single_calls=False):
+        """w: Workload; K_host, V_host: pinned host tensors [n_inst][t_cap][d] (instances layer-major).
+        single_calls: compose every layer step from the single C calls here instead of ap_offload_step."""
         if w.n_local < 1:
             raise ValueError("the newest block must be a forced local block (n_local >= 1)")
         if not (K_host.is_pinned() and V_host.is_pinned()):
@@ -34,6 +35,7 @@ class OffloadRun:
         self.dev = torch.device(device)
         self.ipl = w.batch * w.kv_heads                     # instances per layer
         self.rebase_every = rebase_every
+        self.single_calls = single_calls
         self.copy_stream = torch.cuda.Stream(device=self.dev)
         self.K_host, self.V_host = K_host, V_host
         self.n_pushed = 0
@@ -57,6 +59,7 @@ class OffloadRun:
             L.pool_K = torch.zeros((n * w.k_blocks, w.block, w.head_dim), dtype=w.torch_dtype(), device=self.dev)
             L.pool_V = torch.zeros_like(L.pool_K)
             L.table = torch.zeros((n, nbc), dtype=i32, device=self.dev)
+            L.state = torch.zeros((L.ctx.prefetch_state_bytes() // 4,), dtype=i32, device=self.dev)
             L.K_host = K_host[l * n:(l + 1) * n]
             L.V_host = V_host[l * n:(l + 1) * n]
             L.selected = torch.cuda.Event()
@@ -91,14 +94,19 @@ class OffloadRun:
         L.selected.record(cur)
         self.copy_stream.wait_event(L.selected)
         with torch.cuda.stream(self.copy_stream):
-            L.ctx.prefetch_blocks(L.K_host, L.V_host, t_avail, nb_next, L.idx, L.cnt, L.pool_K, L.pool_V, L.table)
+            L.ctx.prefetch_blocks(L.K_host, L.V_host, t_avail, nb_next, L.idx, L.cnt, L.pool_K, L.pool_V, L.table,
+                                  L.state)
             L.staged.record(self.copy_stream)
 
     def start(self, t_first):
         """After the warm-up pushes: select and stage the blocks of the first decode step (context t_first)."""
         self.n_pushed_layer = self.n_pushed
         for L in self.layers:
-            self._select_and_fetch(L, t_first, AP_PRED_REBASE, t_first - 1)
+            if self.single_calls:
+                self._select_and_fetch(L, t_first, AP_PRED_REBASE, t_first - 1)
+            else:
+                L.ctx.offload_begin(L.hist, self.n_pushed, L.K_host, L.V_host, t_first, L.idx, L.cnt, L.pred, L.pstate,
+                                    L.pool_K, L.pool_V, L.table, L.state, L.ws, self.copy_stream)
 
     def step(self, q, k_new, v_new, t, calibrate=False):
         """One decode step at context length t (the new token has index t - 1).
@@ -107,8 +115,13 @@ class OffloadRun:
         n_after = self.n_pushed + 1
         mode = AP_PRED_REBASE if n_after % self.rebase_every == 0 else AP_PRED_ADVANCE
         for l, L in enumerate(self.layers):
+            if not self.single_calls:
+                L.ctx.offload_step(L.hist, self.n_pushed, self._sl(q, l), self._sl(k_new, l), self._sl(v_new, l),
+                                   L.K_host, L.V_host, t, calibrate, L.out, L.idx, L.cnt, L.pred, L.pstate, mode,
+                                   L.pool_K, L.pool_V, L.table, L.state, L.row, L.ws, self.copy_stream)
+                continue
             cur.wait_event(L.staged)
-            L.ctx.append_kv(self._sl(k_new, l), self._sl(v_new, l), t - 1, L.idx, L.cnt, L.pool_K, L.pool_V)
+            L.ctx.append_kv(self._sl(k_new, l), self._sl(v_new, l), t - 1, L.table, L.state, L.pool_K, L.pool_V)
             L.ctx.set_block_table(L.table, self.ipl * self.w.k_blocks)
             L.ctx.sparse_decode(self._sl(q, l), L.pool_K, L.pool_V, t, L.idx, L.cnt, L.out, L.row, L.ws)
             if calibrate:
@@ -133,6 +146,11 @@ class OffloadRun:
             if self.n_pushed - H + r < 0:
                 h[:, r, :] = 0
         return h
+
+    def blocks_fetched(self) -> int:
+        """Blocks copied from the full cache since the start (all layers and instances); synchronises."""
+        k = self.w.k_blocks
+        return int(sum(L.state.view(self.ipl, 3 * k + 4)[:, 3 * k + 1].sum().item() for L in self.layers))
 
     def out(self):
         return torch.cat([L.out for L in self.layers])

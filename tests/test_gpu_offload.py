@@ -18,10 +18,17 @@ def _pinned(x):
     return h
 
 
+def _expected_block(K, i, blk, b, t_avail):
+    e = K[i, blk * b:(blk + 1) * b].clone()
+    e[max(0, min(b, t_avail - blk * b)):] = 0          # rows of tokens >= t_avail are staged as zeros
+    return e
+
+
 @pytest.mark.parametrize("src", ["pinned", "device"])
 @pytest.mark.parametrize("dtype,d,b", [("bf16", 128, 16), ("f32", 64, 8), ("bf16", 64, 32)])
 def test_prefetch_blocks_and_append(src, dtype, d, b):
-    """Pool slots, block table, zero-filled future rows and the appended row, bit for bit."""
+    """Two selections in a row: slots, block table, zero-filled future rows, the appended row, and that a block
+    which stays selected is neither moved nor fetched again - all bit for bit."""
     dev = _dev()
     ap = _ap()
     n_inst, k, nb_cap = 5, 6, 40
@@ -33,49 +40,83 @@ def test_prefetch_blocks_and_append(src, dtype, d, b):
     K = torch.randn((n_inst, t_cap, d), generator=g).to(tdt)
     V = torch.randn((n_inst, t_cap, d), generator=g).to(tdt)
     Ks, Vs = (_pinned(K), _pinned(V)) if src == "pinned" else (K.to(dev), V.to(dev))
-    t_next = 29 * b + 3                       # context length the selection is for; its token has index t_next - 1
-    nb = (t_next + b - 1) // b
     rng = np.random.default_rng(11)
-    idx_h = np.full((n_inst, k), -7, dtype=np.int32)
-    cnt_h = np.array([k, k, k - 2, 0, k], dtype=np.int32)
-    for i in range(n_inst):
-        c = cnt_h[i]
-        if c:
-            pick = np.sort(rng.choice(nb - 1, size=c - 1, replace=False))
-            idx_h[i, :c] = np.concatenate([pick, [nb - 1]])
-    idx_h[4, cnt_h[4] - 1] = nb - 2           # instance 4 does not select the newest block: nothing is appended
-    idx = torch.from_numpy(idx_h).to(dev)
-    cnt = torch.from_numpy(cnt_h).to(dev)
     pool_K = torch.full((n_inst * k, b, d), 9.0, dtype=tdt, device=dev)
     pool_V = torch.full((n_inst * k, b, d), 9.0, dtype=tdt, device=dev)
     table = torch.full((n_inst, nb_cap), -1, dtype=torch.int32, device=dev)
-    ctx.prefetch_blocks(Ks, Vs, t_next - 1, nb, idx, cnt, pool_K, pool_V, table)
-    k_new = K[:, t_next - 1, :].contiguous().to(dev)
-    v_new = V[:, t_next - 1, :].contiguous().to(dev)
-    ctx.append_kv(k_new, v_new, t_next - 1, idx, cnt, pool_K, pool_V)
-    torch.cuda.synchronize()
-    pk, pv, tb = pool_K.cpu(), pool_V.cpu(), table.cpu().numpy()
-    exp_table = np.full((n_inst, nb_cap), -1, dtype=np.int32)
-    for i in range(n_inst):
-        for p in range(k):
-            slot = i * k + p
-            if p >= cnt_h[i]:
-                assert torch.all(pk[slot] == 9.0) and torch.all(pv[slot] == 9.0), "slot beyond cnt was written"
+    state = torch.zeros((ctx.prefetch_state_bytes() // 4,), dtype=torch.int32, device=dev)
+    stride = 3 * k + 4
+    assert state.numel() == n_inst * stride
+
+    def make_selection(nb, cnt_h, keep_from=None):
+        idx_h = np.full((n_inst, k), -7, dtype=np.int32)
+        for i in range(n_inst):
+            c = cnt_h[i]
+            if not c:
                 continue
-            blk = idx_h[i, p]
-            exp_table[i, blk] = slot
-            ek = K[i, blk * b:(blk + 1) * b].clone()
-            ev = V[i, blk * b:(blk + 1) * b].clone()
-            first_missing = max(0, min(b, (t_next - 1) - blk * b))      # rows of tokens >= t_avail
-            ek[first_missing:] = 0
-            ev[first_missing:] = 0
-            if blk == nb - 1 and p == cnt_h[i] - 1:                      # the appended row
-                r = (t_next - 1) % b
-                ek[r] = K[i, t_next - 1]
-                ev[r] = V[i, t_next - 1]
-            assert torch.equal(pk[slot].view(torch.uint8), ek.view(torch.uint8)), f"K inst {i} pos {p}"
-            assert torch.equal(pv[slot].view(torch.uint8), ev.view(torch.uint8)), f"V inst {i} pos {p}"
-    assert np.array_equal(tb, exp_table)
+            kept = [] if keep_from is None else [x for x in keep_from[i] if x >= 0 and x < nb - 1][:c // 2]
+            rest = [x for x in range(nb - 1) if x not in kept]
+            pick = list(rng.choice(rest, size=c - 1 - len(kept), replace=False))
+            idx_h[i, :c] = np.array(sorted(kept + pick) + [nb - 1], dtype=np.int32)
+        return idx_h
+
+    holds = {}                                            # (inst, block) -> slot, as the test expects it
+    content = {}                                          # (inst, block) -> (K block, V block) expected in the pool
+    total_fetched = np.zeros(n_inst, dtype=np.int64)
+    prev_idx = None
+    for call, t_next in enumerate([29 * b + 3, 29 * b + 4, 30 * b + 1]):   # the last one opens a new block
+        nb = (t_next + b - 1) // b
+        cnt_h = np.array([k, k, k - 2, 0, k], dtype=np.int32)
+        idx_h = make_selection(nb, cnt_h, prev_idx)
+        if call == 0:
+            idx_h[4, cnt_h[4] - 1] = nb - 2               # instance 4 leaves out the newest block: nothing is appended
+        prev_idx = idx_h
+        idx = torch.from_numpy(idx_h).to(dev)
+        cnt = torch.from_numpy(cnt_h).to(dev)
+        ctx.prefetch_blocks(Ks, Vs, t_next - 1, nb, idx, cnt, pool_K, pool_V, table, state)
+        k_new = K[:, t_next - 1, :].contiguous().to(dev)
+        v_new = V[:, t_next - 1, :].contiguous().to(dev)
+        ctx.append_kv(k_new, v_new, t_next - 1, table, state, pool_K, pool_V)
+        torch.cuda.synchronize()
+        pk, pv, tb = pool_K.cpu(), pool_V.cpu(), table.cpu().numpy()
+        st = state.cpu().numpy().reshape(n_inst, stride)
+        for i in range(n_inst):
+            sel = [int(x) for x in idx_h[i, :cnt_h[i]]]
+            old = {blk: sl for (ii, blk), sl in holds.items() if ii == i}
+            misses = [blk for blk in sel if blk not in old]
+            total_fetched[i] += len(misses)
+            assert st[i, 3 * k] == len(misses) and st[i, 3 * k + 1] == total_fetched[i], f"call {call} inst {i}"
+            slots = []
+            for blk in sel:
+                sl = tb[i, blk] - i * k
+                assert 0 <= sl < k and st[i, sl] == blk + 1, f"call {call} inst {i} block {blk}: bad slot"
+                if blk in old:
+                    assert sl == old[blk], "a block that stayed selected was moved"
+                else:
+                    content[(i, blk)] = (_expected_block(K, i, blk, b, t_next - 1), _expected_block(V, i, blk, b, t_next - 1))
+                slots.append(sl)
+            assert len(set(slots)) == len(slots), "two selected blocks share a slot"
+            for blk in list(old):                         # blocks whose slot was taken over are gone
+                if st[i, old[blk]] != blk + 1:
+                    del holds[(i, blk)]
+            for blk, sl in zip(sel, slots):
+                holds[(i, blk)] = sl
+            if (t_next - 1) // b in sel:                  # the appended row
+                ek, ev = content[(i, (t_next - 1) // b)]
+                ek[(t_next - 1) % b] = K[i, t_next - 1]
+                ev[(t_next - 1) % b] = V[i, t_next - 1]
+            for blk, sl in zip(sel, slots):
+                ek, ev = content[(i, blk)]
+                assert torch.equal(pk[i * k + sl].view(torch.uint8), ek.view(torch.uint8)), f"call {call} K inst {i} block {blk}"
+                assert torch.equal(pv[i * k + sl].view(torch.uint8), ev.view(torch.uint8)), f"call {call} V inst {i} block {blk}"
+        assert torch.all(pk[3 * k:4 * k] == 9.0), "an instance with an empty selection was written"
+    assert total_fetched[0] < 3 * k, "nothing was re-used across the three selections"
+    # zeroing the state empties the cache: the same selection is fetched in full again
+    state.zero_()
+    ctx.prefetch_blocks(Ks, Vs, t_next - 1, nb, idx, cnt, pool_K, pool_V, table, state)
+    torch.cuda.synchronize()
+    st = state.cpu().numpy().reshape(n_inst, stride)
+    assert st[:, 3 * k].tolist() == cnt_h.tolist()
 
 
 def test_prefetch_refuses_pageable_host_memory():
@@ -88,21 +129,24 @@ def test_prefetch_refuses_pageable_host_memory():
     cnt = torch.zeros((1,), dtype=torch.int32, device=dev)
     pool = torch.zeros((2, 16, 64), device=dev)
     table = torch.zeros((1, 4), dtype=torch.int32, device=dev)
+    state = torch.zeros((ctx.prefetch_state_bytes() // 4,), dtype=torch.int32, device=dev)
     lib = ap.load_library()
     rc = lib.ap_prefetch_blocks(ctx._h, pageable.data_ptr(), pageable.data_ptr(), 10, 1, idx.data_ptr(), cnt.data_ptr(),
-                                pool.data_ptr(), pool.data_ptr(), table.data_ptr(), None)
+                                pool.data_ptr(), pool.data_ptr(), table.data_ptr(), state.data_ptr(), None)
     assert rc == ap.AP_ERR_ARG
 
 
-def test_offload_lockstep_vs_oracle():
-    """Every step of the prefetching schedule against the oracle started from the GPU's own history."""
+@pytest.mark.parametrize("single_calls", [False, True])
+def test_offload_lockstep_vs_oracle(single_calls):
+    """Every step of the prefetching schedule against the oracle started from the GPU's own history; once through
+    ap_offload_begin / ap_offload_step, once composed from the single calls."""
     dev = _dev()
     from paper_2502_04077_amd.offload import OffloadRun
     w = small("offload", layers=3, batch=1, kv_heads=2, g=4, head_dim=128, t0=1010, budget_tokens=256, hist_len=16,
               steps=40, calib_every=8)
     K, V = kv_cache(w, dev)
     K_host, V_host = _pinned(K), _pinned(V)
-    run = OffloadRun(w, K_host, V_host, dev, rebase_every=24)
+    run = OffloadRun(w, K_host, V_host, dev, rebase_every=24, single_calls=single_calls)
     blob = predictor_weights(w)
     run.set_weights(blob)
     wts = orc.PredictorWeights.from_blob(blob, w.c1, w.c2)
