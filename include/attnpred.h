@@ -57,6 +57,8 @@ extern "C" {
 #define AP_PRED_REBASE 0  /* evaluate the full H x nb tile; (re)writes pstate if one is given        */
 #define AP_PRED_ADVANCE 1 /* pstate is valid for n_pushed - 1 rows: move it forward by one row       */
 #define AP_PRED_HOLD 2    /* pstate is already valid for n_pushed rows: use it as it is              */
+#define AP_PRED_SKIP 3    /* ap_step with AP_STEP_REUSE_SELECTION only: do not run the predictor     */
+#define AP_STEP_REUSE_SELECTION 16 /* OR-ed into ap_step's pred_mode: keep the previous step's selection  */
 
 typedef struct ap_ctx ap_ctx; /* opaque host object; owns only the device copy of the weights */
 
@@ -67,7 +69,7 @@ typedef struct ap_config {
   int32_t block;    /* b: power of two, 8..64                                                       */
   int32_t hist_len; /* H: 1..256                                                                    */
   int32_t t_cap;    /* token capacity of K/V, a multiple of b                                       */
-  int32_t k_blocks; /* k = B / b, n_sink + n_local <= k, k * b <= 4096                              */
+  int32_t k_blocks; /* k = B / b, n_sink + n_local <= k <= 4096; k = t_cap / b gives dense attention   */
   int32_t n_sink;   /* forced leading blocks  (Sec. 4.1: prefix tokens are part of the budget)      */
   int32_t n_local;  /* forced trailing blocks (Sec. 4.1: local tokens are part of the budget)       */
   int32_t c1, c2;   /* predictor channels; compiled pairs: (4,4) (8,8) (16,32)                      */
@@ -139,6 +141,14 @@ int ap_predict_incremental(ap_ctx* ctx, const float* hist, int64_t n_pushed, int
 int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx, int32_t* cnt,
                    void* ws, void* stream);
 
+/* Sec. 3.3 (last sentence of "Distribution Error Calibration"): the positions S are predicted and updated only
+ * every several steps.  This carries a selection made for nb_prev blocks over to a context of nb_cur >=
+ * nb_prev blocks without new scores, in place: the picks below the local window stay, the local window moves
+ * to the last n_local blocks of the current context, blocks of the old local window that fell out of it are
+ * dropped (sink blocks always stay), and at most k entries result.  nb_cur <= k selects every block. */
+int ap_refresh_selection(ap_ctx* ctx, int32_t nb_prev, int32_t nb_cur, int32_t* idx, int32_t* cnt,
+                         void* stream);
+
 /* Block-sparse decode attention (Sec. 3.1 restricted to the tokens of the selected blocks;
  * Algorithm 1 step 6 is implicit: whole blocks are read) plus Algorithm 1 steps 1-2 as a
  * by-product.  The caller has appended the new token's K/V, t_cur counts it; tokens >= t_cur of
@@ -168,7 +178,11 @@ int ap_update_history(ap_ctx* ctx, float* hist, int64_t n_pushed, const float* r
  * straight into ring slot n_pushed % R.  Equivalent to ap_predict_incremental (ap_predict if pstate
  * is NULL), ap_select_topk, ap_sparse_decode and ap_update_history in that order, with
  * nb_prev = ceil((t_cur - 1) / b): decoding appends one token per step.
- * pred, idx and cnt are outputs as in the single calls. */
+ * pred, idx and cnt are outputs as in the single calls.
+ * pred_mode | AP_STEP_REUSE_SELECTION: idx / cnt hold the previous step's selection and are carried over with
+ * ap_refresh_selection instead of being re-made; the predictor still runs in the given mode (which keeps
+ * pstate current, one ADVANCE per pushed row) unless the mode is AP_PRED_SKIP, after which the next
+ * predicting step has to REBASE. */
 int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* K,
             const void* V, int32_t t_cur, float* out, int32_t* idx, int32_t* cnt, float* pred,
             float* pstate, int32_t pred_mode, void* ws, void* stream);

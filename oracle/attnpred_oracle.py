@@ -147,6 +147,24 @@ def select_blocks(pred: np.ndarray, nb: int, k: int, n_sink: int, n_local: int) 
     return np.array(sorted(chosen), dtype=np.int64)
 
 
+def refresh_selection(prev: np.ndarray, nb_prev: int, nb: int, k: int, n_sink: int, n_local: int) -> np.ndarray:
+    """A selection made for nb_prev blocks, re-used for a context of nb >= nb_prev blocks on a step that does
+    not predict (Sec. 3.3: the positions S are predicted and updated only every several steps).  The paper
+    does not say what happens to the forced blocks meanwhile; the reading taken here keeps the budget split
+    of Sec. 4.1 valid at every step: the predicted picks stay as they are, the local window moves with the
+    context (the last n_local blocks of the current length), and a block that has dropped out of the local
+    window is not kept.  If the context has no more than k blocks every block is selected; if the old
+    selection was such an all-blocks one and no longer fits, its highest-numbered blocks below the local
+    window are dropped.
+    """
+    if nb <= k:
+        return np.arange(nb, dtype=np.int64)
+    old_local = set(range(nb_prev - n_local, nb_prev)) if nb_prev > k else set()
+    keep = sorted(int(j) for j in prev if int(j) < nb - n_local and (int(j) not in old_local or int(j) < n_sink))
+    keep = keep[:k - n_local]
+    return np.array(keep + list(range(nb - n_local, nb)), dtype=np.int64)
+
+
 def expand_blocks(blocks: np.ndarray, b: int, t: int) -> np.ndarray:
     """Algorithm 1 step 6: block indices -> token indices {i*b .. i*b+b-1}, clipped to t tokens."""
     tok = (np.asarray(blocks, dtype=np.int64)[:, None] * b + np.arange(b)[None, :]).ravel()
@@ -209,16 +227,20 @@ class StepResult:
 
 
 def decode_step(hist, q, K, V, t: int, wts: PredictorWeights, *, b: int, k: int, n_sink: int,
-                n_local: int, calibrate: bool) -> StepResult:
+                n_local: int, calibrate: bool, reuse=None) -> StepResult:
     """predict -> select -> sparse attention -> pooled row (dense on a calibration step) -> push.
 
     `K`, `V` already hold the new token (t includes it).  On a calibration step only the row
     stored in the history comes from dense attention; the output still uses the sparse set
-    ("Distribution Error Calibration").
+    ("Distribution Error Calibration").  reuse = (blocks, nb_prev) of an earlier step makes this a step
+    that does not update the positions (Sec. 3.3): the selection is that one, refreshed.
     """
     nb = -(-t // b)
     pred = predict(hist, nb, wts)
-    blocks = select_blocks(pred, nb, k, n_sink, n_local)
+    if reuse is None:
+        blocks = select_blocks(pred, nb, k, n_sink, n_local)
+    else:
+        blocks = refresh_selection(reuse[0], reuse[1], nb, k, n_sink, n_local)
     out, A = sparse_attention(q, K, V, blocks, b, t)
     row = dense_row(q, K, b, t) if calibrate else pooled_row(A, b)
     return StepResult(pred, blocks, out, row, history_push(hist, row))

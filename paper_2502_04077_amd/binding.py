@@ -15,13 +15,14 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libattnpred.so")
 
 AP_F32, AP_BF16 = 0, 1
-AP_PRED_REBASE, AP_PRED_ADVANCE, AP_PRED_HOLD = 0, 1, 2
+AP_PRED_REBASE, AP_PRED_ADVANCE, AP_PRED_HOLD, AP_PRED_SKIP = 0, 1, 2, 3
+AP_STEP_REUSE_SELECTION = 16
 AP_FLAG_PREDICTOR_FP32 = 1
 AP_OK, AP_ERR_ARG, AP_ERR_ALIGN, AP_ERR_RANGE, AP_ERR_HIP, AP_ERR_UNSUPPORTED, AP_ERR_STATE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_set_block_table",
-    "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
+    "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_refresh_selection", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
     "ap_prefetch_state_bytes", "ap_prefetch_blocks", "ap_append_kv", "ap_offload_begin", "ap_offload_step", "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
 
@@ -65,6 +66,7 @@ def load_library() -> C.CDLL:
     lib.ap_predict.argtypes = [vp, vp, i64, i32, vp, vp, vp]
     lib.ap_predict_incremental.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.ap_select_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    lib.ap_refresh_selection.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.ap_sparse_decode.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ap_calibrate.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.ap_update_history.argtypes = [vp, vp, i64, vp, vp]
@@ -171,6 +173,9 @@ class Context:
 
     def select_topk(self, pred, nb_cur, idx, cnt, ws) -> None:
         _check(self._lib.ap_select_topk(self._h, _ptr(pred), nb_cur, _ptr(idx), _ptr(cnt), _ptr(ws), _stream()))
+
+    def refresh_selection(self, nb_prev, nb_cur, idx, cnt) -> None:
+        _check(self._lib.ap_refresh_selection(self._h, nb_prev, nb_cur, _ptr(idx), _ptr(cnt), _stream()))
 
     def sparse_decode(self, q, K, V, t_cur, idx, cnt, out, row, ws) -> None:
         _check(self._lib.ap_sparse_decode(self._h, _ptr(q), _ptr(K), _ptr(V), t_cur, _ptr(idx), _ptr(cnt),

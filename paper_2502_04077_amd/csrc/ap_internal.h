@@ -93,6 +93,9 @@ hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void
                                 size_t row_stride, float* ws, hipStream_t st);
 hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row,
                             float* ws, hipStream_t st);
+// Carries a selection made for nb_prev blocks over to nb_cur blocks without new scores (in place).
+hipError_t launch_refresh_selection(const Shape& s, int nb_prev, int nb_cur, int32_t* idx, int32_t* cnt,
+                                    hipStream_t st);
 // Stages the selected blocks of the full cache (pinned host or device memory) that the pool does not hold yet,
 // into slots freed by blocks that left the selection; records slots in `table` and in `state`
 // (int32 [n_inst][prefetch_state_stride]); rows of tokens >= t_avail are zero-filled.

@@ -70,7 +70,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   if (c->head_dim != 64 && c->head_dim != 128) return AP_ERR_UNSUPPORTED;
   if (c->kv_dtype != AP_F32 && c->kv_dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
   if (c->hist_len > 256) return AP_ERR_UNSUPPORTED;
-  if ((int64_t)c->k_blocks * c->block > 4096) return AP_ERR_UNSUPPORTED;
+  if (c->k_blocks > 4096) return AP_ERR_UNSUPPORTED;
   const bool chan_ok = (c->c1 == 4 && c->c2 == 4) || (c->c1 == 8 && c->c2 == 8) || (c->c1 == 16 && c->c2 == 32);
   if (!chan_ok) return AP_ERR_UNSUPPORTED;
   if (c->n_inst > 65535) return AP_ERR_UNSUPPORTED;     // instances ride on gridDim.y
@@ -84,6 +84,13 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   s.predictor_mfma = (((c->c1 == 8 && c->c2 == 8) || (c->c1 == 16 && c->c2 == 32)) &&
                       !(c->flags & AP_FLAG_PREDICTOR_FP32)) ? 1 : 0;
   s.n_split = ap::choose_split(s);
+  {
+    // Dynamic LDS of the attention workgroup (sparse_lds_floats) and of the combine kernel must fit 64 KiB.
+    const size_t nblk = s.n_split == 1 ? s.k : (s.k + s.n_split - 1) / s.n_split;
+    const size_t attn = (size_t)s.g * nblk * s.b + (size_t)ap::kAttnWaves * s.g * s.d + (size_t)s.g * nblk + 3 * nblk + 2 * s.g;
+    const size_t comb = (size_t)s.n_split * s.g + 2 * (size_t)s.k;
+    if (attn * sizeof(float) > 65536 || comb * sizeof(float) > 65536) { delete ctx; return AP_ERR_UNSUPPORTED; }
+  }
   const int chunk_blocks = ap::kCalibChunkTokens / s.b;
   s.calib_chunks = (s.nb_cap + chunk_blocks - 1) / chunk_blocks;
   if ((size_t)s.calib_chunks * s.g * sizeof(float) > 60000) { delete ctx; return AP_ERR_UNSUPPORTED; }
@@ -301,6 +308,15 @@ int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx,
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+int ap_refresh_selection(ap_ctx* ctx, int32_t nb_prev, int32_t nb_cur, int32_t* idx, int32_t* cnt, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  const Shape& s = ctx->s;
+  if (nb_prev < 1 || nb_prev > nb_cur || nb_cur > s.nb_cap) return AP_ERR_RANGE;
+  hipError_t e = ap::launch_refresh_selection(s, nb_prev, nb_cur, idx, cnt, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, int32_t t_cur,
                      const int32_t* idx, const int32_t* cnt, float* out, float* row, void* ws, void* stream) {
   if (ctx == nullptr) return AP_ERR_ARG;
@@ -353,14 +369,25 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
   if (pstate != nullptr && !aligned16(pstate)) return AP_ERR_ALIGN;
   const Shape& s = ctx->s;
   if (!ctx->have_weights) return AP_ERR_STATE;
-  if (pred_mode != AP_PRED_REBASE && pred_mode != AP_PRED_ADVANCE && pred_mode != AP_PRED_HOLD) return AP_ERR_ARG;
+  const bool reuse = (pred_mode & AP_STEP_REUSE_SELECTION) != 0;
+  pred_mode &= ~AP_STEP_REUSE_SELECTION;
+  if (pred_mode != AP_PRED_REBASE && pred_mode != AP_PRED_ADVANCE && pred_mode != AP_PRED_HOLD &&
+      !(reuse && pred_mode == AP_PRED_SKIP))
+    return AP_ERR_ARG;
   if (n_pushed < 0 || t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
   const int nb_cur = (t_cur + s.b - 1) / s.b;
   const int nb_prev = t_cur > 1 ? (t_cur - 1 + s.b - 1) / s.b : 1;   // one token is appended per step
   hipStream_t st = static_cast<hipStream_t>(stream);
-  int rc = run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, pred_mode, pstate, pred, st);
-  if (rc != AP_OK) return rc;
-  if (ap::launch_select(s, 0, s.n_inst, pred, nb_cur, idx, cnt, st) != hipSuccess) return AP_ERR_HIP;
+  if (pred_mode != AP_PRED_SKIP) {
+    int rc = run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, pred_mode, pstate, pred, st);
+    if (rc != AP_OK) return rc;
+  }
+  if (reuse) {
+    if (nb_cur != nb_prev && ap::launch_refresh_selection(s, nb_prev, nb_cur, idx, cnt, st) != hipSuccess)
+      return AP_ERR_HIP;
+  } else if (ap::launch_select(s, 0, s.n_inst, pred, nb_cur, idx, cnt, st) != hipSuccess) {
+    return AP_ERR_HIP;
+  }
   const int slot = (int)(n_pushed % s.R);
   float* slot_row = hist + (size_t)slot * s.nb_cap;
   if (ap::launch_sparse_decode(s, 0, s.n_inst, q, K, V, t_cur, idx, cnt, out, slot_row, (size_t)s.R * s.nb_cap,

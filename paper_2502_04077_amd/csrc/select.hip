@@ -15,7 +15,63 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
                         s_mem);
 }
 
+// A selection made for nb_prev blocks, carried over to nb_cur >= nb_prev blocks without new scores: the picks
+// below the local window stay (ascending order is kept by an ordered compaction), the blocks of the old local
+// window are dropped unless they are sink blocks, at most k - n_local entries survive, and the last n_local
+// blocks of the current context are appended.  One workgroup per instance; smem: k ints.
+__global__ __launch_bounds__(kSelThreads) void refresh_selection_kernel(int nb_prev, int nb_cur, int k, int n_sink,
+                                                                        int n_local, int32_t* __restrict__ idx,
+                                                                        int32_t* __restrict__ cnt) {
+  extern __shared__ int s_in[];
+  __shared__ int s_wsum[kSelWaves];
+  const int inst = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  int32_t* out = idx + (size_t)inst * k;
+  if (nb_cur <= k) {
+    for (int j = tid; j < nb_cur; j += kSelThreads) out[j] = j;
+    if (tid == 0) cnt[inst] = nb_cur;
+    return;
+  }
+  const int c = min(max(cnt[inst], 0), k);
+  for (int p = tid; p < c; p += kSelThreads) s_in[p] = out[p];
+  __syncthreads();
+  const int hi = nb_cur - n_local, cap = k - n_local;
+  const int old_lo = nb_prev > k ? nb_prev - n_local : nb_prev;      // old local window [old_lo, nb_prev)
+  int taken = 0;
+  for (int p0 = 0; p0 < c; p0 += kSelThreads) {
+    const int p = p0 + tid;
+    bool keep = false;
+    int j = 0;
+    if (p < c) {
+      j = s_in[p];
+      keep = j >= 0 && j < hi && (j < n_sink || j < old_lo || j >= nb_prev);
+    }
+    const unsigned long long m = __ballot(keep);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wsum[wave] = __popcll(m);
+    __syncthreads();
+    int base = 0, total = 0;
+    for (int w = 0; w < kSelWaves; ++w) {
+      if (w < wave) base += s_wsum[w];
+      total += s_wsum[w];
+    }
+    const int pos = taken + base + before;
+    if (keep && pos < cap) out[pos] = j;
+    taken += total;
+    __syncthreads();
+  }
+  const int m = min(taken, cap);
+  for (int j = tid; j < n_local; j += kSelThreads) out[m + j] = hi + j;
+  if (tid == 0) cnt[inst] = m + n_local;
+}
+
 }  // namespace
+
+hipError_t launch_refresh_selection(const Shape& s, int nb_prev, int nb_cur, int32_t* idx, int32_t* cnt,
+                                    hipStream_t st) {
+  refresh_selection_kernel<<<dim3(s.n_inst), kSelThreads, sizeof(int) * s.k, st>>>(nb_prev, nb_cur, s.k, s.n_sink,
+                                                                                 s.n_local, idx, cnt);
+  return hipGetLastError();
+}
 
 hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred, int nb_cur, int32_t* idx,
                          int32_t* cnt, hipStream_t st) {

@@ -531,3 +531,113 @@ def test_paged_kv_equals_contiguous(kw):
     pag.ctx.sparse_decode(q, K, V, t, pag.idx, pag.cnt, pag.out, pag.row, pag.ws)
     torch.cuda.synchronize()
     assert torch.equal(ref.out, pag.out)
+
+
+# --------------------------------------------------------------------------------------------- refresh / dense
+@pytest.mark.parametrize("k,n_sink,n_local,nb_prev,nb_cur", [
+    (64, 4, 4, 2049, 2049), (64, 4, 4, 2049, 2050), (64, 4, 4, 2040, 2047), (16, 1, 2, 70, 71), (16, 0, 1, 16, 17),
+    (16, 1, 2, 10, 12), (300, 2, 3, 400, 401), (8, 1, 7, 20, 22), (8, 3, 2, 9, 10),
+])
+def test_refresh_selection_bit_exact(k, n_sink, n_local, nb_prev, nb_cur):
+    dev = _dev()
+    ap = _ap()
+    n_inst, b = 7, 16
+    nb_cap = nb_cur + 3
+    ctx = ap.Context(n_inst=n_inst, g=1, head_dim=64, block=b, hist_len=8, t_cap=nb_cap * b, k_blocks=k,
+                     n_sink=n_sink, n_local=n_local, c1=4, c2=4, kv_dtype="f32")
+    rng = np.random.default_rng(k * 7 + nb_cur)
+    idx_h = np.full((n_inst, k), -7, dtype=np.int32)
+    cnt_h = np.zeros(n_inst, dtype=np.int32)
+    prev = []
+    for i in range(n_inst):
+        s0 = orc.select_blocks(rng.standard_normal(nb_prev), nb_prev, k, n_sink, n_local)
+        prev.append(s0)
+        idx_h[i, :len(s0)] = s0
+        cnt_h[i] = len(s0)
+    idx = torch.from_numpy(idx_h).to(dev)
+    cnt = torch.from_numpy(cnt_h).to(dev)
+    ctx.refresh_selection(nb_prev, nb_cur, idx, cnt)
+    torch.cuda.synchronize()
+    got_idx, got_cnt = idx.cpu().numpy(), cnt.cpu().numpy()
+    for i in range(n_inst):
+        exp = orc.refresh_selection(prev[i], nb_prev, nb_cur, k, n_sink, n_local)
+        assert got_cnt[i] == len(exp)
+        assert got_idx[i, :got_cnt[i]].tolist() == exp.tolist(), f"instance {i}"
+
+
+def test_lockstep_refresh_interval():
+    """The selection is re-made on every 4th step only; in between it is carried over while the context grows
+    across block boundaries.  Every step against the oracle told to do the same."""
+    dev = _dev()
+    w = small("refresh", kv_heads=3, g=4, head_dim=128, t0=1015, budget_tokens=256, hist_len=16, steps=40, calib_every=8)
+    run = _run(w, dev)
+    run.refresh_every = 4
+    K, V = kv_cache(w, dev)
+    wts = orc.PredictorWeights.from_blob(predictor_weights(w), w.c1, w.c2)
+    H, b = w.hist_len, w.block
+    Kc = [to_f64(K[i]) for i in range(w.n_inst)]
+    Vc = [to_f64(V[i]) for i in range(w.n_inst)]
+    for j in range(H):
+        run.warmup_calibrate(queries(w, j - H, dev), K, w.t0 - H + 1 + j)
+    last = [None] * w.n_inst
+    carried = 0
+    for s in range(w.steps):
+        t = w.t_at(s)
+        nb = run.nb(t)
+        q = queries(w, s, dev)
+        calib = w.is_calibration_step(s)
+        selects = run.selects_now(t)
+        before = run.logical_history().cpu().numpy().astype(np.float64)
+        if s % 2 == 0:
+            run.step(q, K, V, t, calibrate=calib)
+        else:
+            run.step_unfused(q, K, V, t, calibrate=calib)
+        torch.cuda.synchronize()
+        after = run.logical_history().cpu().numpy()
+        pred, idx, cnt, out = (x.cpu().numpy() for x in (run.pred, run.idx, run.cnt, run.out))
+        for i in range(w.n_inst):
+            qi = to_f64(q[i])
+            assert_close(pred[i, :nb], orc.predict(before[i], nb, wts), f"step {s} inst {i} pred")   # state stays current
+            got_idx = idx[i, :cnt[i]]
+            if selects:
+                exp_idx = orc.select_blocks(pred[i, :nb].astype(np.float64), nb, w.k_blocks, w.n_sink, w.n_local)
+            else:
+                exp_idx = orc.refresh_selection(last[i][0], last[i][1], nb, w.k_blocks, w.n_sink, w.n_local)
+                carried += 1
+            assert got_idx.tolist() == exp_idx.tolist(), f"step {s} inst {i}: selection differs (selects={selects})"
+            last[i] = (got_idx.copy(), nb)
+            ref = orc.decode_step(before[i], qi, Kc[i], Vc[i], t, wts, b=b, k=w.k_blocks, n_sink=w.n_sink,
+                                  n_local=w.n_local, calibrate=calib, reuse=None if selects else (got_idx, nb))
+            if not selects:
+                assert ref.blocks.tolist() == got_idx.tolist()
+                for h in range(w.g):
+                    assert_close(out[i, h], ref.out[h], f"step {s} inst {i} head {h} out")
+                row = np.zeros(run.nb_cap)
+                row[:nb] = ref.row
+                assert_close(after[i, H - 1], row, f"step {s} inst {i} pushed row")
+            else:
+                ref_out, A = orc.sparse_attention(qi, Kc[i], Vc[i], got_idx, b, t)
+                for h in range(w.g):
+                    assert_close(out[i, h], ref_out[h], f"step {s} inst {i} head {h} out")
+    assert carried == w.n_inst * (w.steps - w.steps // 4)
+
+
+def test_dense_layers_match_dense_attention():
+    """A budget of all blocks through the same kernels: attention over the whole context (32 splits per instance)."""
+    dev = _dev()
+    from paper_2502_04077_amd.runner import DenseRun
+    w = small("dense", layers=2, batch=1, kv_heads=2, g=4, head_dim=128, t0=9000, budget_tokens=256, hist_len=16, steps=3)
+    K, V = kv_cache(w, dev)
+    run = DenseRun(w, 2, dev)
+    for s in range(w.steps):
+        t = w.t_at(s)
+        q = queries(w, s, dev)
+        run.step(q, K, V, t)
+        torch.cuda.synchronize()
+        out = run.out.cpu().numpy()
+        nb = (t + w.block - 1) // w.block
+        for i in (0, w.n_inst - 1):
+            ref_out, A = orc.sparse_attention(to_f64(q[i]), to_f64(K[i]), to_f64(V[i]), np.arange(nb), w.block, t)
+            for h in range(w.g):
+                assert_close(out[i, h], ref_out[h], f"step {s} inst {i} head {h}")
+            assert_close(run.row[i, :nb].cpu().numpy(), orc.dense_row(to_f64(q[i]), to_f64(K[i]), w.block, t), "dense row")

@@ -51,12 +51,22 @@ def test_create_accepts_the_five_configurations():
 @pytest.mark.parametrize("kw,code", [
     (dict(n_inst=0), -1), (dict(t_cap=1000), -1), (dict(n_sink=40, n_local=40), -1), (dict(hist_len=0), -1),
     (dict(block=12), -5), (dict(block=128, t_cap=128 * 300), -5), (dict(g=3), -5), (dict(head_dim=96), -5),
-    (dict(c1=8, c2=16), -5), (dict(kv_dtype=7), -5), (dict(k_blocks=512), -5), (dict(hist_len=300), -5),
+    (dict(c1=8, c2=16), -5), (dict(kv_dtype=7), -5), (dict(k_blocks=5000), -5), (dict(hist_len=300), -5),
     (dict(n_inst=70000), -5),
 ])
 def test_create_rejects_bad_configurations(kw, code):
     rc, h = _create(**kw)
     assert rc == code and not h.value
+
+
+def test_dense_budget_is_accepted():
+    """k = t_cap / b (every block selected) is a valid configuration: attention over the whole context."""
+    from workloads import CONFIGS
+    w = CONFIGS["cfg2"]
+    c = ap.Context(n_inst=128, g=w.g, head_dim=w.head_dim, block=w.block, hist_len=w.hist_len, t_cap=w.t_cap,
+                   k_blocks=w.nb_cap, n_sink=0, n_local=0, c1=w.c1, c2=w.c2, kv_dtype=w.kv_dtype)
+    assert c.workspace_bytes() > 0
+    c.close()
 
 
 def test_null_and_misaligned_pointers_are_refused_before_any_launch():

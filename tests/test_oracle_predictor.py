@@ -208,3 +208,42 @@ def test_paper_feature_map_footprint(ctx, key):
     per_px = y1.shape[0] + y2.shape[0]
     mib = heads * H * nb * per_px * 4 / 2**20
     assert abs(mib - g[key]) / g[key] < 0.02
+
+
+# --------------------------------------------------------------------------------------------- refresh
+def test_refresh_selection_worked_example():
+    """k = 6 with 1 sink and 2 local blocks, selection made at 10 blocks: [0 | 3 5 6 | 8 9]."""
+    prev = np.array([0, 3, 5, 6, 8, 9])
+    assert orc.refresh_selection(prev, 10, 10, 6, 1, 2).tolist() == [0, 3, 5, 6, 8, 9]      # same length: unchanged
+    assert orc.refresh_selection(prev, 10, 11, 6, 1, 2).tolist() == [0, 3, 5, 6, 9, 10]     # 8 left the window
+    assert orc.refresh_selection(prev, 10, 13, 6, 1, 2).tolist() == [0, 3, 5, 6, 11, 12]
+    assert orc.refresh_selection(np.arange(5), 5, 6, 6, 1, 2).tolist() == [0, 1, 2, 3, 4, 5]  # fits the budget: all
+    # an all-blocks selection that stops fitting: the highest blocks below the local window go
+    assert orc.refresh_selection(np.arange(6), 6, 7, 6, 1, 2).tolist() == [0, 1, 2, 3, 5, 6]
+
+
+def test_refresh_selection_properties_and_composition():
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        k = int(rng.integers(4, 20))
+        n_sink = int(rng.integers(0, 3))
+        n_local = int(rng.integers(1, 4))
+        if n_sink + n_local > k:
+            continue
+        nb0 = int(rng.integers(k + 1, 80))
+        pred = rng.standard_normal(nb0)
+        s0 = orc.select_blocks(pred, nb0, k, n_sink, n_local)
+        nb1 = nb0 + int(rng.integers(0, 4))
+        nb2 = nb1 + int(rng.integers(0, 4))
+        s1 = orc.refresh_selection(s0, nb0, nb1, k, n_sink, n_local)
+        s2 = orc.refresh_selection(s1, nb1, nb2, k, n_sink, n_local)
+        direct = orc.refresh_selection(s0, nb0, nb2, k, n_sink, n_local)
+        assert s2.tolist() == direct.tolist(), "carrying over in two hops differs from one hop"
+        for s, nb in ((s1, nb1), (s2, nb2)):
+            assert np.all(np.diff(s) > 0) and s[0] >= 0 and s[-1] == nb - 1
+            assert set(range(n_sink)) <= set(s.tolist()) and set(range(nb - n_local, nb)) <= set(s.tolist())
+            mid_prev = set(s0.tolist()) - set(range(nb0 - n_local, nb0))
+            assert set(s.tolist()) - set(range(nb - n_local, nb)) <= mid_prev, "a block that was never predicted appeared"
+        if nb1 == nb0:
+            assert s1.tolist() == s0.tolist()
+        assert len(s1) == k and len(s2) == k, "the budget is spent in full at every step"
