@@ -185,6 +185,10 @@ def main():
     ap_.add_argument("--offload", action="store_true",
                      help="K/V in pinned host memory with cross-token prefetching (Sec. 3.4); one 8B-shaped model, "
                           "batch 1, 32 layers, 32K context; prints its own JSON line")
+    ap_.add_argument("--refresh-every", type=int, default=1,
+                     help="re-make the selection on every N-th step only and carry it over in between (Sec. 3.3)")
+    ap_.add_argument("--dense-layers", type=int, default=0,
+                     help="the first N layers attend to the whole cache in every step (Sec. 4.1 keeps two uncompressed)")
     ap_.add_argument("--planted", action="store_true",
                      help="with --offload: keys and queries with the planted sink / stripe / local / slash structure of "
                           "cfg4 instead of plain Gaussian ones")
@@ -198,22 +202,31 @@ def main():
         return main_offload(args)
 
     import torch
-    from paper_2502_04077_amd.runner import DecodeRun
+    from paper_2502_04077_amd.runner import DecodeRun, DenseRun
     from workloads import CONFIGS, kv_cache, predictor_weights, queries
 
-    w = CONFIGS[args.workload]
+    w_all = CONFIGS[args.workload]
     total_steps = args.warmup + args.steps
-    if total_steps > w.steps:
-        w = w.with_(steps=total_steps)
+    if total_steps > w_all.steps:
+        w_all = w_all.with_(steps=total_steps)
+    if not 0 <= args.dense_layers < w_all.layers:
+        print("bench.py: --dense-layers must leave at least one sparse layer", file=sys.stderr)
+        sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    run = DecodeRun(w, dev)
+    K_all, V_all = kv_cache(w_all, dev)
+    # Instances are layer-major: the dense layers are the first nd instances, everything below is the sparse rest.
+    nd = args.dense_layers * w_all.batch * w_all.kv_heads
+    w = w_all.with_(layers=w_all.layers - args.dense_layers)
+    K, V = K_all[nd:], V_all[nd:]
+    dense = DenseRun(w_all, args.dense_layers, dev) if nd else None
+    run = DecodeRun(w, dev, refresh_every=args.refresh_every)
     run.set_weights(predictor_weights(w))
-    K, V = kv_cache(w, dev)
     H = w.hist_len
     for j in range(H):                                    # prefill tail fills the history
-        run.warmup_calibrate(queries(w, j - H, dev), K, w.t0 - H + 1 + j)
-    qs = [queries(w, s, dev) for s in range(total_steps)]
+        run.warmup_calibrate(queries(w_all, j - H, dev)[nd:], K, w.t0 - H + 1 + j)
+    qs_all = [queries(w_all, s, dev) for s in range(total_steps)]
+    qs = [q[nd:] for q in qs_all]
     torch.cuda.synchronize()
 
     cpu = None
@@ -223,6 +236,8 @@ def main():
     modes = []
 
     def one_step(s):
+        if dense is not None:
+            dense.step(qs_all[s][:nd], K_all[:nd], V_all[:nd], w.t_at(s))
         return run.step(qs[s], K, V, w.t_at(s), calibrate=w.is_calibration_step(s))
 
     for s in range(args.warmup):
@@ -272,6 +287,23 @@ def main():
             kern_ms[n] = sum(a.elapsed_time(b) for a, b in m) / len(m)
         kern_ms = {k: round(v, 5) for k, v in kern_ms.items()}
 
+    # Attention over the whole cache with the same kernel (a budget of all blocks), for the sparse-versus-dense ratio.
+    dense_ms = None
+    if not args.no_breakdown:
+        full = dense if (dense is not None and nd == w_all.n_inst) else DenseRun(w_all, w_all.layers, dev)
+        t_d = w.t_at(args.warmup + args.steps // 2)
+        full.step(qs_all[0], K_all, V_all, t_d)
+        torch.cuda.synchronize()
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        d0.record()
+        for _ in range(3):
+            full.step(qs_all[0], K_all, V_all, t_d)
+        d1.record()
+        torch.cuda.synchronize()
+        dense_ms = d0.elapsed_time(d1) / 3
+        del full
+        torch.cuda.empty_cache()
+
     # Read bandwidth this machine reaches with a plain streaming kernel over the K cache (same run).
     from paper_2502_04077_amd import stream_read
     sink = torch.zeros((65536 * 16,), dtype=torch.uint8, device=dev)
@@ -316,16 +348,21 @@ def main():
         "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.kv_dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": w.name, "instances": w.n_inst, "layers": w.layers, "batch": w.batch,
+        "config": {"workload": w.name, "instances": w_all.n_inst, "layers": w_all.layers, "batch": w.batch,
                    "kv_heads": w.kv_heads, "q_per_kv": w.g, "head_dim": w.head_dim, "context": w.t0,
                    "block": w.block, "history": w.hist_len, "budget_tokens": w.budget_tokens,
                    "predictor_channels": [w.c1, w.c2], "calibration_every": w.calib_every,
                    "calibration_steps_in_timed_region": n_calib, "predictor": "incremental",
-                   "predictor_rebase_every": run.rebase_every, "rebase_steps_in_timed_region": n_rebase},
+                   "predictor_rebase_every": run.rebase_every, "rebase_steps_in_timed_region": n_rebase,
+                   "selection_refresh_every": args.refresh_every, "dense_layers": args.dense_layers},
         # algorithmic bytes of everything in the timed region (steps, calibrations, re-bases) over its wall time
         "step_hbm_frac": timed_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_GB": timed_bytes / args.steps / 1e9,
         "kernel_ms": kern_ms,
+        # the same attention kernel over every block of the context (all instances), and what the budget saves
+        "dense_attention": None if dense_ms is None else {
+            "ms": dense_ms, "GBs": 2 * w_all.n_inst * t_mid * w_all.head_dim * (2 if w_all.kv_dtype == "bf16" else 4) / dense_ms / 1e6,
+            "sparse_decode_speedup": dense_ms / (kern_ms["sparse_decode"] * w_all.n_inst / w.n_inst) if kern_ms else None},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
