@@ -185,6 +185,9 @@ def main():
     ap_.add_argument("--offload", action="store_true",
                      help="K/V in pinned host memory with cross-token prefetching (Sec. 3.4); one 8B-shaped model, "
                           "batch 1, 32 layers, 32K context; prints its own JSON line")
+    ap_.add_argument("--no-dense-figure", action="store_true",
+                     help="skip the launches of the attention kernel over the whole context (they share the sparse "
+                          "kernel's name in a profile)")
     ap_.add_argument("--refresh-every", type=int, default=1,
                      help="re-make the selection on every N-th step only and carry it over in between (Sec. 3.3)")
     ap_.add_argument("--dense-layers", type=int, default=0,
@@ -289,7 +292,7 @@ def main():
 
     # Attention over the whole cache with the same kernel (a budget of all blocks), for the sparse-versus-dense ratio.
     dense_ms = None
-    if not args.no_breakdown:
+    if not args.no_breakdown and not args.no_dense_figure:
         full = dense if (dense is not None and nd == w_all.n_inst) else DenseRun(w_all, w_all.layers, dev)
         t_d = w.t_at(args.warmup + args.steps // 2)
         full.step(qs_all[0], K_all, V_all, t_d)
