@@ -293,7 +293,7 @@ def main():
     # Attention over the whole cache with the same kernel (a budget of all blocks), for the sparse-versus-dense ratio.
     dense_ms = None
     if not args.no_breakdown and not args.no_dense_figure:
-        full = dense if (dense is not None and nd == w_all.n_inst) else DenseRun(w_all, w_all.layers, dev)
+        full = DenseRun(w_all, w_all.layers, dev)
         t_d = w.t_at(args.warmup + args.steps // 2)
         full.step(qs_all[0], K_all, V_all, t_d)
         torch.cuda.synchronize()

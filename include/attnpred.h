@@ -69,7 +69,7 @@ typedef struct ap_config {
   int32_t block;    /* b: power of two, 8..64                                                       */
   int32_t hist_len; /* H: 1..256                                                                    */
   int32_t t_cap;    /* token capacity of K/V, a multiple of b                                       */
-  int32_t k_blocks; /* k = B / b, n_sink + n_local <= k <= 4096; k = t_cap / b gives dense attention   */
+  int32_t k_blocks; /* k = B / b, n_sink + n_local <= k <= 16384; k = t_cap / b gives dense attention  */
   int32_t n_sink;   /* forced leading blocks  (Sec. 4.1: prefix tokens are part of the budget)      */
   int32_t n_local;  /* forced trailing blocks (Sec. 4.1: local tokens are part of the budget)       */
   int32_t c1, c2;   /* predictor channels; compiled pairs: (4,4) (8,8) (16,32)                      */

@@ -70,7 +70,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   if (c->head_dim != 64 && c->head_dim != 128) return AP_ERR_UNSUPPORTED;
   if (c->kv_dtype != AP_F32 && c->kv_dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
   if (c->hist_len > 256) return AP_ERR_UNSUPPORTED;
-  if (c->k_blocks > 4096) return AP_ERR_UNSUPPORTED;
+  if (c->k_blocks > 16384) return AP_ERR_UNSUPPORTED;
   const bool chan_ok = (c->c1 == 4 && c->c2 == 4) || (c->c1 == 8 && c->c2 == 8) || (c->c1 == 16 && c->c2 == 32);
   if (!chan_ok) return AP_ERR_UNSUPPORTED;
   if (c->n_inst > 65535) return AP_ERR_UNSUPPORTED;     // instances ride on gridDim.y
@@ -88,7 +88,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
     // Dynamic LDS of the attention workgroup (sparse_lds_floats) and of the combine kernel must fit 64 KiB.
     const size_t nblk = s.n_split == 1 ? s.k : (s.k + s.n_split - 1) / s.n_split;
     const size_t attn = (size_t)s.g * nblk * s.b + (size_t)ap::kAttnWaves * s.g * s.d + (size_t)s.g * nblk + 3 * nblk + 2 * s.g;
-    const size_t comb = (size_t)s.n_split * s.g + 2 * (size_t)s.k;
+    const size_t comb = (size_t)s.n_split * s.g + (size_t)s.k;
     if (attn * sizeof(float) > 65536 || comb * sizeof(float) > 65536) { delete ctx; return AP_ERR_UNSUPPORTED; }
   }
   const int chunk_blocks = ap::kCalibChunkTokens / s.b;

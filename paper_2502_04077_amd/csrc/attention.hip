@@ -17,8 +17,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs
   const int inst = a.inst0 + blockIdx.x;
   const int cnt = min(max(a.cnt[inst], 0), a.k);
   float* s_scale = smem;                               // [n_split][G]  exp(m_s - M) / L
-  float* s_rowval = s_scale + a.n_split * G;           // [k]
-  int* s_idx = reinterpret_cast<int*>(s_rowval + a.k); // [k]
+  int* s_idx = reinterpret_cast<int*>(s_scale + a.n_split * G);   // [k]
 
   for (int j = threadIdx.x; j < cnt; j += kAttnThreads)
     s_idx[j] = min(max(a.idx[(size_t)inst * a.k + j], 0), a.nb_cur - 1);
@@ -45,16 +44,15 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs
       v = fmaf(a.part_acc[((size_t)inst * a.n_split + s) * G * D + o], s_scale[s * G + h], v);
     a.out[(size_t)inst * G * D + o] = v;
   }
-  for (int jb = threadIdx.x; jb < cnt; jb += kAttnThreads) {
+  // pooled probability of list position jb: max over heads of (block max relative to its split) * split scale
+  write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, cnt, [&](int jb) {
     const int s = jb / a.blk_per_split;
     float mx = 0.f;
 #pragma unroll
     for (int h = 0; h < G; ++h)
       mx = fmaxf(mx, a.part_bmp[((size_t)inst * G + h) * a.k + jb] * s_scale[s * G + h]);
-    s_rowval[jb] = mx;
-  }
-  __syncthreads();
-  write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, cnt, s_rowval);
+    return mx;
+  });
 }
 
 struct CalibArgs {
@@ -141,7 +139,7 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   sparse_decode_kernel<T, D, G><<<dim3(a.n_split, ninst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.n_split == 1) return e;
-  const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G + a.k) + sizeof(int) * a.k;
+  const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G) + sizeof(int) * a.k;
   sparse_combine_kernel<D, G><<<dim3(ninst), kAttnThreads, lds2, st>>>(a);
   return hipGetLastError();
 }

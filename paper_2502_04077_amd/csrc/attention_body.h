@@ -226,16 +226,17 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
   __syncthreads();
 }
 
-// Writes one instance's pooled row: rowval[pos] at column idx[pos] (idx ascending), 0 elsewhere.
+// Writes one instance's pooled row: value_at(pos) at column idx[pos] (idx ascending), 0 elsewhere.
+template <class ValueAt>
 __device__ __forceinline__ void write_row(float* __restrict__ row, int nb_cap, const int* s_idx, int cnt,
-                                 const float* s_rowval) {
+                                          ValueAt value_at) {
   for (int j = threadIdx.x; j < nb_cap; j += blockDim.x) {
     int lo = 0, hi = cnt;                       // first position with idx >= j
     while (lo < hi) {
       const int mid = (lo + hi) >> 1;
       if (s_idx[mid] < j) lo = mid + 1; else hi = mid;
     }
-    row[j] = (lo < cnt && s_idx[lo] == j) ? s_rowval[lo] : 0.f;
+    row[j] = (lo < cnt && s_idx[lo] == j) ? value_at(lo) : 0.f;
   }
 }
 
@@ -364,7 +365,7 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
       s_rowval[jb] = mx;
     }
     __syncthreads();
-    write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, nblk, s_rowval);
+    write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, nblk, [&](int pos) { return s_rowval[pos]; });
   } else {
     const size_t ps = (size_t)inst * a.n_split + split;
     for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {

@@ -4,15 +4,14 @@
 namespace ap {
 namespace {
 
-template <int KPT>
-__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* __restrict__ pred, int nb_cap,
-                                                                  int nb_cur, int k, int n_sink, int n_local,
-                                                                  int inst0, int32_t* __restrict__ idx,
-                                                                  int32_t* __restrict__ cnt) {
-  __shared__ uint32_t s_mem[kSelScratchWords];
+template <int KPT, int NT>
+__global__ __launch_bounds__(NT) void select_topk_kernel(const float* __restrict__ pred, int nb_cap, int nb_cur, int k,
+                                                         int n_sink, int n_local, int inst0,
+                                                         int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
+  __shared__ uint32_t s_mem[sel_scratch_words<NT>()];
   const int inst = inst0 + blockIdx.x;
-  select_topk_body<KPT>(pred + (size_t)inst * nb_cap, nb_cur, k, n_sink, n_local, idx + (size_t)inst * k, cnt + inst,
-                        s_mem);
+  select_topk_body<KPT, NT>(pred + (size_t)inst * nb_cap, nb_cur, k, n_sink, n_local, idx + (size_t)inst * k,
+                            cnt + inst, s_mem);
 }
 
 // A selection made for nb_prev blocks, carried over to nb_cur >= nb_prev blocks without new scores: the picks
@@ -23,6 +22,7 @@ __global__ __launch_bounds__(kSelThreads) void refresh_selection_kernel(int nb_p
                                                                         int n_local, int32_t* __restrict__ idx,
                                                                         int32_t* __restrict__ cnt) {
   extern __shared__ int s_in[];
+  constexpr int kSelWaves = kSelThreads / kWave;
   __shared__ int s_wsum[kSelWaves];
   const int inst = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   int32_t* out = idx + (size_t)inst * k;
@@ -77,9 +77,18 @@ hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred
                          int32_t* cnt, hipStream_t st) {
   const int n_mid = nb_cur - s.n_sink - s.n_local;
   const dim3 grid(ninst);
-#define AP_SELECT(KPT) \
-  select_topk_kernel<KPT><<<grid, kSelThreads, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local, inst0, idx, cnt)
-  if (n_mid <= 8 * kSelThreads) AP_SELECT(8);            // the variants differ only in unrolled trip count
+#define AP_SELECT_NT(KPT, NT) \
+  select_topk_kernel<KPT, NT><<<grid, NT, 0, st>>>(pred, s.nb_cap, nb_cur, s.k, s.n_sink, s.n_local, inst0, idx, cnt)
+#define AP_SELECT(KPT) AP_SELECT_NT(KPT, kSelThreads)
+  // Few instances with long rows: 1024 threads per instance cut the serial chain of every pass (a 256-thread
+  // workgroup walks 32 keys per thread at 128K context while half of the chip has no workgroup at all).
+  if (ninst <= 512 && n_mid > 4 * kSelThreads) {
+    if (n_mid <= 4 * kSelThreadsWide) AP_SELECT_NT(4, kSelThreadsWide);
+    else if (n_mid <= 8 * kSelThreadsWide) AP_SELECT_NT(8, kSelThreadsWide);
+    else if (n_mid <= 16 * kSelThreadsWide) AP_SELECT_NT(16, kSelThreadsWide);
+    else AP_SELECT_NT(0, kSelThreadsWide);
+  }
+  else if (n_mid <= 8 * kSelThreads) AP_SELECT(8);       // the variants differ only in unrolled trip count
   else if (n_mid <= 9 * kSelThreads) AP_SELECT(9);
   else if (n_mid <= 10 * kSelThreads) AP_SELECT(10);
   else if (n_mid <= 12 * kSelThreads) AP_SELECT(12);
@@ -88,6 +97,7 @@ hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred
   else if (n_mid <= 32 * kSelThreads) AP_SELECT(32);
   else AP_SELECT(0);
 #undef AP_SELECT
+#undef AP_SELECT_NT
   return hipGetLastError();
 }
 

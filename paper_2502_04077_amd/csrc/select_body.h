@@ -14,10 +14,10 @@
 namespace ap {
 namespace {
 
-constexpr int kSelScratchWords = 256 + 3 * (256 / kWave) + 4;
-
-constexpr int kSelThreads = 256;
-constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kSelThreads = 256;           // workgroup size of the common variant
+constexpr int kSelThreadsWide = 1024;      // few instances, long rows: more threads per instance
+constexpr int kSelBins = 256;              // radix of one pass; the first kSelBins threads own one bin each
+template <int NT> constexpr int sel_scratch_words() { return kSelBins + 3 * (NT / kWave) + 4; }
 
 __device__ __forceinline__ uint32_t score_key(float x) {
   uint32_t u = __float_as_uint(x);
@@ -43,19 +43,20 @@ __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool acti
   if (active) atomicAdd(&hist[bin], 1u);
 }
 
-// Selection for one instance by one workgroup of kSelThreads threads.
+// Selection for one instance by one workgroup of NT threads (a multiple of kSelBins).
 //   p        the instance's scores (nb_cur valid entries)
 //   out      the instance's k index slots, cnt_out its count
-//   s_mem    kSelScratchWords words of LDS, free for this call (the caller synchronises before)
-template <int KPT>   // keys per thread held in registers; 0 = re-read the scores in every pass
+//   s_mem    sel_scratch_words<NT>() words of LDS, free for this call (the caller synchronises before)
+template <int KPT, int NT>   // KPT: keys per thread held in registers; 0 = re-read the scores in every pass
 __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, int nb_cur, int k, int n_sink, int n_local,
                                         int32_t* __restrict__ out, int32_t* __restrict__ cnt_out, uint32_t* s_mem) {
-  uint32_t* s_hist = s_mem;                     // [256]
-  uint32_t* s_wsum = s_mem + 256;               // [kSelWaves]
+  constexpr int kSelThreads = NT, kSelWaves = NT / kWave;
+  uint32_t* s_hist = s_mem;                     // [kSelBins]
+  uint32_t* s_wsum = s_mem + kSelBins;          // [kSelWaves]
   uint32_t* s_wgt = s_wsum + kSelWaves;         // [kSelWaves]
   uint32_t* s_weq = s_wgt + kSelWaves;          // [kSelWaves]
-  uint32_t& s_bin = s_mem[256 + 3 * kSelWaves];
-  uint32_t& s_above = s_mem[256 + 3 * kSelWaves + 1];
+  uint32_t& s_bin = s_mem[kSelBins + 3 * kSelWaves];
+  uint32_t& s_above = s_mem[kSelBins + 3 * kSelWaves + 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
   if (nb_cur <= k) {                                    // everything fits the budget
@@ -86,7 +87,7 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
   uint32_t need = (uint32_t)k_mid;                      // still to take among keys matching prefix
   if (k_mid > 0) {
     for (int shift = 24; shift >= 0; shift -= 8) {
-      s_hist[tid] = 0;
+      if (tid < kSelBins) s_hist[tid] = 0;
       __syncthreads();
 #pragma unroll NK
       for (int i = 0; i < n_iter; ++i) {                   // uniform trip count: ballots need every lane
@@ -96,21 +97,27 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
         hist_add(s_hist, (key >> shift) & 255u, match);
       }
       __syncthreads();
-      // Suffix sums over bins: thread r handles bin 255 - r, inclusive scan in that order.
-      const uint32_t c = s_hist[255 - tid];
-      uint32_t incl = c;
+      // Suffix sums over bins: thread r < kSelBins handles bin 255 - r, inclusive scan in that order
+      // (whole waves take or skip these branches).
+      uint32_t c = 0, incl = 0;
+      if (tid < kSelBins) {
+        c = s_hist[kSelBins - 1 - tid];
+        incl = c;
 #pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += up;
+        for (int o = 1; o < kWave; o <<= 1) {
+          const uint32_t up = __shfl_up(incl, o, kWave);
+          if (lane >= o) incl += up;
+        }
+        if (lane == kWave - 1) s_wsum[wave] = incl;
       }
-      if (lane == kWave - 1) s_wsum[wave] = incl;
       __syncthreads();
-      uint32_t base = 0;
-      for (int w = 0; w < wave; ++w) base += s_wsum[w];
-      incl += base;                                     // keys in bins >= 255 - tid
-      const uint32_t excl = incl - c;                   // keys in bins >  255 - tid
-      if (excl < need && need <= incl) { s_bin = 255 - tid; s_above = excl; }
+      if (tid < kSelBins) {
+        uint32_t base = 0;
+        for (int w = 0; w < wave; ++w) base += s_wsum[w];
+        incl += base;                                   // keys in bins >= 255 - tid
+        const uint32_t excl = incl - c;                 // keys in bins >  255 - tid
+        if (excl < need && need <= incl) { s_bin = kSelBins - 1 - tid; s_above = excl; }
+      }
       __syncthreads();
       prefix = (prefix << 8) | s_bin;
       need -= s_above;

@@ -59,15 +59,20 @@ def small(name="t", **kw):
 
 
 # --------------------------------------------------------------------------------------------- select
-@pytest.mark.parametrize("nb,k,ns,nl,mode", [
-    (128, 16, 1, 2, "ties"), (2048, 64, 4, 4, "normal"), (2051, 64, 4, 4, "ties"), (8200, 128, 4, 4, "normal"),
-    (300, 64, 0, 0, "allequal"), (64, 64, 4, 4, "normal"), (10, 64, 4, 4, "normal"), (65, 64, 4, 4, "ties"),
-    (500, 8, 4, 4, "normal"), (700, 33, 3, 5, "signedzero"), (1000, 40, 2, 2, "negative"),
+@pytest.mark.parametrize("nb,k,ns,nl,mode,n_inst", [
+    (128, 16, 1, 2, "ties", 5), (2048, 64, 4, 4, "normal", 5), (2051, 64, 4, 4, "ties", 5),
+    (8200, 128, 4, 4, "normal", 5), (300, 64, 0, 0, "allequal", 5), (64, 64, 4, 4, "normal", 5),
+    (10, 64, 4, 4, "normal", 5), (65, 64, 4, 4, "ties", 5), (500, 8, 4, 4, "normal", 5),
+    (700, 33, 3, 5, "signedzero", 5), (1000, 40, 2, 2, "negative", 5),
+    # many instances keep 256 threads per instance; few instances with long rows take 1024
+    (2051, 64, 4, 4, "ties", 600), (2400, 64, 4, 4, "normal", 520), (8200, 128, 4, 4, "ties", 513),
+    (9000, 64, 4, 4, "normal", 515), (5000, 128, 4, 4, "ties", 3), (12000, 200, 1, 1, "normal", 2),
+    (20000, 64, 4, 4, "ties", 2), (4104, 64, 4, 4, "allequal", 1),
 ])
-def test_select_topk_bit_exact(nb, k, ns, nl, mode):
+def test_select_topk_bit_exact(nb, k, ns, nl, mode, n_inst):
     dev = _dev()
     ap = _ap()
-    n_inst, b = 5, 16
+    b = 16
     nb_cap = nb + 3
     ctx = ap.Context(n_inst=n_inst, g=1, head_dim=64, block=b, hist_len=4, t_cap=nb_cap * b, k_blocks=k,
                      n_sink=ns, n_local=nl, c1=4, c2=4, kv_dtype="f32")

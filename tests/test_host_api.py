@@ -51,7 +51,7 @@ def test_create_accepts_the_five_configurations():
 @pytest.mark.parametrize("kw,code", [
     (dict(n_inst=0), -1), (dict(t_cap=1000), -1), (dict(n_sink=40, n_local=40), -1), (dict(hist_len=0), -1),
     (dict(block=12), -5), (dict(block=128, t_cap=128 * 300), -5), (dict(g=3), -5), (dict(head_dim=96), -5),
-    (dict(c1=8, c2=16), -5), (dict(kv_dtype=7), -5), (dict(k_blocks=5000), -5), (dict(hist_len=300), -5),
+    (dict(c1=8, c2=16), -5), (dict(kv_dtype=7), -5), (dict(k_blocks=20000), -5), (dict(hist_len=300), -5),
     (dict(n_inst=70000), -5),
 ])
 def test_create_rejects_bad_configurations(kw, code):
