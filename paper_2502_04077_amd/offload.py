@@ -16,7 +16,7 @@ from __future__ import annotations
 
 import torch
 
-from .binding import AP_PRED_ADVANCE, AP_PRED_REBASE, Context
+from .binding import AP_PRED_ADVANCE, AP_PRED_REBASE, Context, _check, _ptr, _rptr, load_library
 
 
 class _Layer:
@@ -64,8 +64,14 @@ class OffloadRun:
             L.V_host = V_host[l * n:(l + 1) * n]
             L.selected = torch.cuda.Event()
             L.staged = torch.cuda.Event()
+            # addresses that never change, checked once: a 32-layer token step is bound by the host's enqueue rate
+            L.handle = L.ctx._h
+            L.ptrs = {n: _ptr(getattr(L, n)) for n in ("hist", "out", "idx", "cnt", "pred", "pstate", "pool_K", "pool_V",
+                                                       "table", "state", "row", "ws")}
+            L.ptrs["K_host"], L.ptrs["V_host"] = _rptr(L.K_host), _rptr(L.V_host)
             self.layers.append(L)
         self.R, self.nb_cap = R, nbc
+        self._step_fn = load_library().ap_offload_step
 
     def set_weights(self, blob):
         for L in self.layers:
@@ -114,12 +120,20 @@ class OffloadRun:
         cur = torch.cuda.current_stream(self.dev)
         n_after = self.n_pushed + 1
         mode = AP_PRED_REBASE if n_after % self.rebase_every == 0 else AP_PRED_ADVANCE
+        if not self.single_calls:
+            qp, kp, vp = _ptr(q), _ptr(k_new), _ptr(v_new)
+            q_step = self.ipl * self.w.g * self.w.head_dim * q.element_size()
+            kv_step = self.ipl * self.w.head_dim * k_new.element_size()
+            cs, ps, cal = cur.cuda_stream, self.copy_stream.cuda_stream, int(bool(calibrate))
+            for l, L in enumerate(self.layers):
+                P = L.ptrs
+                _check(self._step_fn(L.handle, P["hist"], self.n_pushed, qp + l * q_step, kp + l * kv_step,
+                                     vp + l * kv_step, P["K_host"], P["V_host"], t, cal, P["out"], P["idx"], P["cnt"],
+                                     P["pred"], P["pstate"], mode, P["pool_K"], P["pool_V"], P["table"], P["state"],
+                                     P["row"], P["ws"], cs, ps))
+            self.n_pushed = n_after
+            return
         for l, L in enumerate(self.layers):
-            if not self.single_calls:
-                L.ctx.offload_step(L.hist, self.n_pushed, self._sl(q, l), self._sl(k_new, l), self._sl(v_new, l),
-                                   L.K_host, L.V_host, t, calibrate, L.out, L.idx, L.cnt, L.pred, L.pstate, mode,
-                                   L.pool_K, L.pool_V, L.table, L.state, L.row, L.ws, self.copy_stream)
-                continue
             cur.wait_event(L.staged)
             L.ctx.append_kv(self._sl(k_new, l), self._sl(v_new, l), t - 1, L.table, L.state, L.pool_K, L.pool_V)
             L.ctx.set_block_table(L.table, self.ipl * self.w.k_blocks)
