@@ -49,9 +49,9 @@ extern "C" {
 #define AP_BF16 1
 
 /* ap_config.flags */
-#define AP_FLAG_PREDICTOR_FP32 1 /* keep the incremental predictor's second conv layer in fp32 FMAs.
-                                    Default for 8/8 channels: f16 operands on MFMA with fp32
-                                    accumulation (pred moves by ~1e-5 of its magnitude).            */
+#define AP_FLAG_PREDICTOR_FP32 1 /* evaluate the incremental predictor with fp32 FMAs.  Default for 8/8
+                                    and 16/32 channels: both conv layers on MFMA with f16 operands
+                                    and fp32 accumulation (pred moves by ~1e-4 of its magnitude).   */
 
 /* Predictor evaluation modes (ap_predict_incremental, ap_step). */
 #define AP_PRED_REBASE 0  /* evaluate the full H x nb tile; (re)writes pstate if one is given        */

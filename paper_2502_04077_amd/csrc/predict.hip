@@ -136,12 +136,14 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
 //   bottom o0 = entering row: kh 0,1,2 <- q0,q1,q2    o1 = row H-2: kh 0,1,2 <- q1,q2,q3  o2 = row H-1: kh 0,1 <- q2,q3
 // o0 has the same operand positions in both halves, so the leaving row is evaluated by the same
 // instruction sequence on the same values as when it entered: the two cancel exactly and only the
-// two additions into `state` round.
+// two additions into `state` round (VALU and 8/8 MFMA variants; the 16/32 MFMA variant sums the taps of
+// the two halves in different orders and cancels up to fp32 rounding).
 //
-// Two variants:
-//   VALU  fp32 FMAs, weights through scalar loads (any compiled channel pair);
-//   MFMA  (C1 = C2 = 8) both layers as 32x32x16 f16 MFMA chains with fp32 accumulation, 32 columns at
-//         a time; see predict_inc_mfma_kernel.
+// Variants:
+//   VALU  fp32 FMAs, weights through scalar loads (any compiled channel pair; AP_FLAG_PREDICTOR_FP32);
+//   MFMA  both layers as 32x32x16 f16 MFMA chains with fp32 accumulation, 32 columns at a time:
+//         predict_inc_mfma_body (C1 = C2 = 8, predict_body.h) and predict_inc_mfma16_body (C1 = 16,
+//         C2 = 32, predict_body16.h).
 
 template <int C1, int C2, int HF>
 __device__ __forceinline__ void y2_valu(const Weights<C1, C2>& W, const float* yb, int YW, float (&o)[3][C2]) {
