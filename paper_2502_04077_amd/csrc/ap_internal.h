@@ -39,6 +39,7 @@ struct WsLayout {
   size_t part_bmp;    // [n_inst][g][k]                 per selected block: max prob relative to split max
   size_t cal_ml;      // [n_inst][calib_chunks][g][2]
   size_t cal_bmp;     // [n_inst][g][nb_cap]
+  size_t pred_state;  // [n_inst][nb_cap]               interior state of a full-tile prediction without a caller state
   size_t total;       // floats
 };
 
@@ -59,6 +60,9 @@ __host__ __device__ constexpr int predictor_tap(int half, int out, int q) {
 // scaled by 2^-4.
 constexpr int kMfmaTableFloatOffset = 676;
 constexpr int kMfmaTableHalfs = 2 * 6 * 64 * 8 + 2 * 64 * 8;
+// ... and by the tables of the interior-state kernel (predict_interior.h): layer 2 [step 8][lane 64][8 f16],
+// layer 1 [lane 64][8 f16].
+constexpr int kMfmaInteriorTableHalfs = 8 * 64 * 8 + 64 * 8;
 
 // The same for 16/32 channels (fp32 section: 10*16 + 9*16*32 + 2*32 + 1 = 4833 floats):
 // layer 2 [half 2][pair 8][kw 3][lane 64][8 f16], lane (m = lane % 32, h = lane / 32) holding input channels
@@ -77,6 +81,10 @@ __host__ __device__ constexpr int mfma16_phys(int half, int i) { return (half ==
 // Launchers that take (inst0, ninst) work on instances [inst0, inst0 + ninst) of the same buffers.
 hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                           int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st);
+// Interior state (rows 2..H-3) of every column from scratch on MFMA (8/8 channels, H >= 6); the incremental
+// kernel without an advance then adds the border rows and writes pred.
+hipError_t launch_predict_interior(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                                   int newest_slot, int nb_cur, float* pstate, hipStream_t st);
 // The same evaluation for a handful of columns [col_begin, nb_cur): one wave per (instance, column).
 hipError_t launch_predict_columns(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                                   int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred,

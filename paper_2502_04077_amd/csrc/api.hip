@@ -26,6 +26,7 @@ WsLayout ws_layout(const Shape& s) {
   w.part_bmp = o; o = align4(o + (size_t)s.n_inst * s.g * s.k);
   w.cal_ml = o;   o = align4(o + (size_t)s.n_inst * s.calib_chunks * s.g * 2);
   w.cal_bmp = o;  o = align4(o + (size_t)s.n_inst * s.g * s.nb_cap);
+  w.pred_state = o; o = align4(o + (size_t)s.n_inst * s.nb_cap);
   w.total = o;
   return w;
 }
@@ -151,7 +152,7 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   const float* w3 = b2 + c2;
   const float* b3 = w3 + c2;
   const bool mfma_table = (c1 == 8 && c2 == 8), mfma16_table = (c1 == 16 && c2 == 32);
-  const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + ap::kMfmaTableHalfs / 2
+  const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + (ap::kMfmaTableHalfs + ap::kMfmaInteriorTableHalfs) / 2
                      : mfma16_table ? ap::kMfma16TableFloatOffset + ap::kMfma16TableHalfs / 2 : expect;
   std::vector<float> packed(total, 0.f);
   float* p = packed.data();
@@ -202,6 +203,32 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
           }
           t1[(half * 64 + lane) * 8 + e] = (_Float16)v;
         }
+  }
+  if (mfma_table) {
+    // Interior-state kernel: strips of three output rows o from five y1 rows q (kernel row q - o), and three y1
+    // rows q from five x rows (kernel row xrow - q); no row of it touches the zero padding in time.
+    _Float16* t = reinterpret_cast<_Float16*>(packed.data() + ap::kMfmaTableFloatOffset) + ap::kMfmaTableHalfs;
+    for (int step = 0; step < 8; ++step)
+      for (int lane = 0; lane < 64; ++lane) {
+        const int m = lane % 32, chunk = 2 * step + lane / 32, q = chunk / 3, kw = chunk % 3;
+        const int kh = q - m / 8;
+        for (int ci = 0; ci < 8; ++ci) {
+          float v = 0.f;
+          if (m < 24 && chunk < 15 && kh >= 0 && kh < 3) v = w2[(((size_t)(m % 8) * c1 + ci) * 3 + kh) * 3 + kw];
+          t[(step * 64 + lane) * 8 + ci] = (_Float16)v;
+        }
+      }
+    _Float16* t1 = t + 8 * 64 * 8;
+    for (int lane = 0; lane < 64; ++lane)
+      for (int e = 0; e < 8; ++e) {
+        const int m = lane % 32, k = 8 * (lane / 32) + e;
+        float v = 0.f;
+        if (m < 24 && k < 15) {
+          const int kh = k / 3 - m / 8, kw = k % 3;
+          if (kh >= 0 && kh < 3) v = w1[((m % 8) * 3 + kh) * 3 + kw] * (1.f / 16.f);
+        }
+        t1[lane * 8 + e] = (_Float16)v;
+      }
   }
   if (mfma16_table) {
     // A operands of the 16/32-channel kernel (layout and numbering: ap_internal.h).
@@ -254,10 +281,19 @@ static int newest_slot_of(const Shape& s, int64_t n_pushed) {
 
 // Runs the predictor in the requested mode; shared by ap_predict_incremental and ap_step.
 static int run_predictor(const ap_ctx* ctx, const float* hist, int64_t n_pushed, int nb_cur, int nb_prev, int mode,
-                         float* pstate, float* pred, hipStream_t st) {
+                         float* pstate, float* pred, float* ws, hipStream_t st) {
   const Shape& s = ctx->s;
   const int newest = newest_slot_of(s, n_pushed);
   if (pstate == nullptr || mode == AP_PRED_REBASE || s.H < 6) {
+    if (s.H >= 6 && s.predictor_mfma && s.c1 == 8) {
+      // Full tile on MFMA: the interior state from scratch (into the caller's pstate, or into the workspace when
+      // the caller keeps none), then the borders and the head as in a HOLD call.
+      float* state = pstate != nullptr ? pstate : ws + ap::ws_layout(s).pred_state;
+      if (ap::launch_predict_interior(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, state, st) != hipSuccess ||
+          ap::launch_predict_inc(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, 0, state, pred, st) != hipSuccess)
+        return AP_ERR_HIP;
+      return AP_OK;
+    }
     return ap::launch_predict(s, 0, s.n_inst, ctx->dweights, hist, newest, nb_cur, 0, pstate, pred, st) == hipSuccess
                ? AP_OK : AP_ERR_HIP;
   }
@@ -284,7 +320,7 @@ int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur,
   const Shape& s = ctx->s;
   if (!ctx->have_weights) return AP_ERR_STATE;
   if (n_pushed < 0 || nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
-  return run_predictor(ctx, hist, n_pushed, nb_cur, nb_cur, AP_PRED_REBASE, nullptr, pred,
+  return run_predictor(ctx, hist, n_pushed, nb_cur, nb_cur, AP_PRED_REBASE, nullptr, pred, static_cast<float*>(ws),
                        static_cast<hipStream_t>(stream));
 }
 
@@ -297,7 +333,8 @@ int ap_predict_incremental(ap_ctx* ctx, const float* hist, int64_t n_pushed, int
   if (mode != AP_PRED_REBASE && mode != AP_PRED_ADVANCE && mode != AP_PRED_HOLD) return AP_ERR_ARG;
   if (n_pushed < 0 || nb_cur < 1 || nb_cur > s.nb_cap) return AP_ERR_RANGE;
   if (mode != AP_PRED_REBASE && (nb_prev < 1 || nb_prev > nb_cur)) return AP_ERR_RANGE;
-  return run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, mode, pstate, pred, static_cast<hipStream_t>(stream));
+  return run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, mode, pstate, pred, static_cast<float*>(ws),
+                       static_cast<hipStream_t>(stream));
 }
 
 int ap_select_topk(ap_ctx* ctx, const float* pred, int32_t nb_cur, int32_t* idx, int32_t* cnt, void* ws,
@@ -386,7 +423,7 @@ int ap_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const voi
   const int nb_prev = t_cur > 1 ? (t_cur - 1 + s.b - 1) / s.b : 1;   // one token is appended per step
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (pred_mode != AP_PRED_SKIP) {
-    int rc = run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, pred_mode, pstate, pred, st);
+    int rc = run_predictor(ctx, hist, n_pushed, nb_cur, nb_prev, pred_mode, pstate, pred, static_cast<float*>(ws), st);
     if (rc != AP_OK) return rc;
   }
   if (reuse) {
@@ -450,11 +487,11 @@ static int offload_events(ap_ctx* ctx) {
 static int offload_select_and_fetch(ap_ctx* ctx, const float* hist, int64_t n_pushed, const void* K_src,
                                     const void* V_src, int t_next, int t_avail, int mode, int32_t* idx, int32_t* cnt,
                                     float* pred, float* pstate, void* pool_K, void* pool_V, int32_t* table,
-                                    int32_t* state, hipStream_t cs, hipStream_t ps) {
+                                    int32_t* state, float* ws, hipStream_t cs, hipStream_t ps) {
   const Shape& s = ctx->s;
   const int nb_next = (t_next + s.b - 1) / s.b;
   const int nb_prev = t_next > 1 ? (t_next - 1 + s.b - 1) / s.b : 1;
-  int rc = run_predictor(ctx, hist, n_pushed, nb_next, nb_prev, mode, pstate, pred, cs);
+  int rc = run_predictor(ctx, hist, n_pushed, nb_next, nb_prev, mode, pstate, pred, ws, cs);
   if (rc != AP_OK) return rc;
   if (ap::launch_select(s, 0, s.n_inst, pred, nb_next, idx, cnt, cs) != hipSuccess) return AP_ERR_HIP;
   if (hipEventRecord(ctx->ev_selected, cs) != hipSuccess) return AP_ERR_HIP;
@@ -482,8 +519,8 @@ int ap_offload_begin(ap_ctx* ctx, const float* hist, int64_t n_pushed, const voi
   int rc = offload_events(ctx);
   if (rc != AP_OK) return rc;
   return offload_select_and_fetch(ctx, hist, n_pushed, K_src, V_src, t_first, t_first - 1, AP_PRED_REBASE, idx, cnt, pred,
-                                  pstate, pool_K, pool_V, block_table, state, static_cast<hipStream_t>(compute_stream),
-                                  static_cast<hipStream_t>(copy_stream));
+                                  pstate, pool_K, pool_V, block_table, state, static_cast<float*>(ws),
+                                  static_cast<hipStream_t>(compute_stream), static_cast<hipStream_t>(copy_stream));
 }
 
 int ap_offload_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, const void* k_new, const void* v_new,
@@ -520,7 +557,7 @@ int ap_offload_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, c
   }
   if (t_cur + 1 > s.t_cap) return AP_OK; // the cache is full: no next token to prepare
   return offload_select_and_fetch(ctx, hist, n_pushed + 1, K_src, V_src, t_cur + 1, t_cur, pred_mode, idx, cnt, pred,
-                                  pstate, pool_K, pool_V, block_table, state, cs, ps);
+                                  pstate, pool_K, pool_V, block_table, state, static_cast<float*>(ws), cs, ps);
 }
 
 int ap_stream_read(const void* src, size_t bytes, void* sink, int32_t n_workgroups, void* stream) {

@@ -26,6 +26,7 @@
 // the state, so callers re-base with the full-tile kernel now and then.
 #include "predict_body.h"
 #include "predict_body16.h"
+#include "predict_interior.h"
 
 namespace ap {
 namespace {
@@ -282,6 +283,15 @@ __global__ __launch_bounds__(256) void predict_inc_mfma16_kernel(const float* __
                           gridDim.x, advance, pstate, pred, smem);
 }
 
+__global__ __launch_bounds__(256) void predict_interior_mfma_kernel(const float* __restrict__ hist,
+                                                                    const float* __restrict__ wts_global, int R, int H,
+                                                                    int newest_slot, int nb_cur, int nb_cap, int inst0,
+                                                                    float* __restrict__ pstate) {
+  extern __shared__ __align__(16) float smem[];
+  predict_interior_mfma_body(hist, wts_global, R, H, newest_slot, nb_cur, nb_cap, inst0 + blockIdx.y, blockIdx.x,
+                             gridDim.x, pstate, smem);
+}
+
 // Full evaluation of a few columns (the ones whose state is void after the tile has grown by a block):
 // one wave per (instance, column), lanes are time rows.  A lane gathers the 5 x 5 x neighbourhood of its
 // pixel from the ring and evaluates y1 on the 3 x 3 pixels around it channel by channel, feeding y2.
@@ -409,6 +419,17 @@ hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dwe
   if (s.c1 == 16 && s.c2 == 32)
     return run_full<16, 32>(s, inst0, ninst, dweights, hist, newest_slot, nb_cur, col_begin, pstate, pred, st);
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_predict_interior(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
+                                   int newest_slot, int nb_cur, float* pstate, hipStream_t st) {
+  if (s.c1 != 8 || s.c2 != 8 || s.H < 6) return hipErrorInvalidValue;
+  const int groups = (nb_cur + 4 * kPiOut - 1) / (4 * kPiOut);
+  int chunks = (2048 + s.n_inst - 1) / s.n_inst;         // about eight workgroups per CU when instances are few
+  if (chunks > groups) chunks = groups;
+  predict_interior_mfma_kernel<<<dim3(chunks, ninst), 256, sizeof(float) * kPredInteriorLdsFloats, st>>>(
+      hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, pstate);
+  return hipGetLastError();
 }
 
 hipError_t launch_predict_columns(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
