@@ -71,6 +71,7 @@ constexpr int kMfmaInteriorTableHalfs = 8 * 64 * 8 + 64 * 8;
 // scaled by 2^-4.  Pairs in table order, with staged rows q and outputs o numbered as the kernel does:
 constexpr int kMfma16TableFloatOffset = 4836;
 constexpr int kMfma16TableHalfs = 2 * 24 * 64 * 8 + 2 * 2 * 64 * 8;
+constexpr int kMfma16InteriorTableHalfs = 9 * 64 * 8 + 64 * 8;   // interior-state kernel (predict_interior.h)
 constexpr int kMfma16PairQ[8] = {0, 1, 1, 1, 2, 2, 3, 3};
 constexpr int kMfma16PairO[8] = {0, 0, 1, 2, 0, 2, 1, 2};
 // Kernel numbering -> the numbering predictor_tap uses (rows and outputs 1, 2 swap in the bottom half).
@@ -81,7 +82,7 @@ __host__ __device__ constexpr int mfma16_phys(int half, int i) { return (half ==
 // Launchers that take (inst0, ninst) work on instances [inst0, inst0 + ninst) of the same buffers.
 hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                           int newest_slot, int nb_cur, int col_begin, float* pstate, float* pred, hipStream_t st);
-// Interior state (rows 2..H-3) of every column from scratch on MFMA (8/8 channels, H >= 6); the incremental
+// Interior state (rows 2..H-3) of every column from scratch on MFMA (8/8 or 16/32 channels, H >= 6); the incremental
 // kernel without an advance then adds the border rows and writes pred.
 hipError_t launch_predict_interior(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                                    int newest_slot, int nb_cur, float* pstate, hipStream_t st);

@@ -153,7 +153,8 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   const float* b3 = w3 + c2;
   const bool mfma_table = (c1 == 8 && c2 == 8), mfma16_table = (c1 == 16 && c2 == 32);
   const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + (ap::kMfmaTableHalfs + ap::kMfmaInteriorTableHalfs) / 2
-                     : mfma16_table ? ap::kMfma16TableFloatOffset + ap::kMfma16TableHalfs / 2 : expect;
+                     : mfma16_table ? ap::kMfma16TableFloatOffset + (ap::kMfma16TableHalfs + ap::kMfma16InteriorTableHalfs) / 2
+                     : expect;
   std::vector<float> packed(total, 0.f);
   float* p = packed.data();
   for (int t = 0; t < 9; ++t)
@@ -262,6 +263,29 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
             t1[((half * 2 + rb) * 64 + lane) * 8 + e] = (_Float16)v;
           }
   }
+  if (mfma16_table) {
+    // Interior-state kernel for 16/32 channels: one operand per (kernel row, tap) for layer 2, two y1 rows from four
+    // x rows for layer 1.
+    _Float16* t = reinterpret_cast<_Float16*>(packed.data() + ap::kMfma16TableFloatOffset) + ap::kMfma16TableHalfs;
+    for (int kh = 0; kh < 3; ++kh)
+      for (int kw = 0; kw < 3; ++kw)
+        for (int lane = 0; lane < 64; ++lane)
+          for (int e = 0; e < 8; ++e) {
+            const int co = lane % 32, ci = 8 * (lane / 32) + e;
+            t[(((kh * 3 + kw) * 64) + lane) * 8 + e] = (_Float16)w2[(((size_t)co * c1 + ci) * 3 + kh) * 3 + kw];
+          }
+    _Float16* t1 = t + 9 * 64 * 8;
+    for (int lane = 0; lane < 64; ++lane)
+      for (int e = 0; e < 8; ++e) {
+        const int m = lane % 32, k = 8 * (lane / 32) + e;
+        float v = 0.f;
+        if (k < 12) {
+          const int kh = k / 3 - m / 16, kw = k % 3;
+          if (kh >= 0 && kh < 3) v = w1[((m % 16) * 3 + kh) * 3 + kw] * (1.f / 16.f);
+        }
+        t1[lane * 8 + e] = (_Float16)v;
+      }
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->dweights == nullptr &&
       hipMalloc(reinterpret_cast<void**>(&ctx->dweights), total * sizeof(float)) != hipSuccess) {
@@ -285,7 +309,7 @@ static int run_predictor(const ap_ctx* ctx, const float* hist, int64_t n_pushed,
   const Shape& s = ctx->s;
   const int newest = newest_slot_of(s, n_pushed);
   if (pstate == nullptr || mode == AP_PRED_REBASE || s.H < 6) {
-    if (s.H >= 6 && s.predictor_mfma && s.c1 == 8) {
+    if (s.H >= 6 && s.predictor_mfma) {
       // Full tile on MFMA: the interior state from scratch (into the caller's pstate, or into the workspace when
       // the caller keeps none), then the borders and the head as in a HOLD call.
       float* state = pstate != nullptr ? pstate : ws + ap::ws_layout(s).pred_state;

@@ -292,6 +292,15 @@ __global__ __launch_bounds__(256) void predict_interior_mfma_kernel(const float*
                              gridDim.x, pstate, smem);
 }
 
+__global__ __launch_bounds__(256) void predict_interior_mfma16_kernel(const float* __restrict__ hist,
+                                                                      const float* __restrict__ wts_global, int R,
+                                                                      int H, int newest_slot, int nb_cur, int nb_cap,
+                                                                      int inst0, float* __restrict__ pstate) {
+  extern __shared__ __align__(16) float smem[];
+  predict_interior_mfma16_body(hist, wts_global, R, H, newest_slot, nb_cur, nb_cap, inst0 + blockIdx.y, blockIdx.x,
+                               gridDim.x, pstate, smem);
+}
+
 // Full evaluation of a few columns (the ones whose state is void after the tile has grown by a block):
 // one wave per (instance, column), lanes are time rows.  A lane gathers the 5 x 5 x neighbourhood of its
 // pixel from the ring and evaluates y1 on the 3 x 3 pixels around it channel by channel, feeding y2.
@@ -423,12 +432,17 @@ hipError_t launch_predict(const Shape& s, int inst0, int ninst, const float* dwe
 
 hipError_t launch_predict_interior(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist,
                                    int newest_slot, int nb_cur, float* pstate, hipStream_t st) {
-  if (s.c1 != 8 || s.c2 != 8 || s.H < 6) return hipErrorInvalidValue;
+  const bool c8 = s.c1 == 8 && s.c2 == 8, c16 = s.c1 == 16 && s.c2 == 32;
+  if (!(c8 || c16) || s.H < 6) return hipErrorInvalidValue;
   const int groups = (nb_cur + 4 * kPiOut - 1) / (4 * kPiOut);
   int chunks = (2048 + s.n_inst - 1) / s.n_inst;         // about eight workgroups per CU when instances are few
   if (chunks > groups) chunks = groups;
-  predict_interior_mfma_kernel<<<dim3(chunks, ninst), 256, sizeof(float) * kPredInteriorLdsFloats, st>>>(
-      hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, pstate);
+  if (c8)
+    predict_interior_mfma_kernel<<<dim3(chunks, ninst), 256, sizeof(float) * kPredInteriorLdsFloats, st>>>(
+        hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, pstate);
+  else
+    predict_interior_mfma16_kernel<<<dim3(chunks, ninst), 256, sizeof(float) * kPredInterior16LdsFloats, st>>>(
+        hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, pstate);
   return hipGetLastError();
 }
 
