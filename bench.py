@@ -192,6 +192,8 @@ def main():
                      help="re-make the selection on every N-th step only and carry it over in between (Sec. 3.3)")
     ap_.add_argument("--dense-layers", type=int, default=0,
                      help="the first N layers attend to the whole cache in every step (Sec. 4.1 keeps two uncompressed)")
+    ap_.add_argument("--predictor-channels", type=int, nargs=2, metavar=("C1", "C2"), default=None,
+                     help="hidden channels of the predictor instead of the workload's (16 32 is the paper's own network)")
     ap_.add_argument("--planted", action="store_true",
                      help="with --offload: keys and queries with the planted sink / stripe / local / slash structure of "
                           "cfg4 instead of plain Gaussian ones")
@@ -212,6 +214,8 @@ def main():
     total_steps = args.warmup + args.steps
     if total_steps > w_all.steps:
         w_all = w_all.with_(steps=total_steps)
+    if args.predictor_channels:
+        w_all = w_all.with_(c1=args.predictor_channels[0], c2=args.predictor_channels[1])
     if not 0 <= args.dense_layers < w_all.layers:
         print("bench.py: --dense-layers must leave at least one sparse layer", file=sys.stderr)
         sys.exit(2)
