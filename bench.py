@@ -200,7 +200,7 @@ def main():
     args = ap_.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (instances are independent, "
-              "sharding is described in DESIGN.md but not built).", file=sys.stderr)
+              "sharding across GPUs is not built).", file=sys.stderr)
         sys.exit(2)
 
     if args.offload:
