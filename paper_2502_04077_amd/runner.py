@@ -7,7 +7,7 @@ from __future__ import annotations
 
 import torch
 
-from .binding import AP_PRED_ADVANCE, AP_PRED_HOLD, AP_PRED_REBASE, AP_STEP_REUSE_SELECTION, Context
+from .binding import AP_PRED_ADVANCE, AP_PRED_HOLD, AP_PRED_REBASE, AP_PRED_SKIP, AP_STEP_REUSE_SELECTION, Context
 
 
 class DecodeRun:
@@ -15,9 +15,13 @@ class DecodeRun:
         """incremental: carry the predictor's interior state across steps (ap_predict_incremental)
         and re-evaluate the full tile every `rebase_every` pushes; False evaluates the full tile
         on every step.  refresh_every: the selection is re-made on every refresh_every-th step and
-        carried over (ap_refresh_selection) on the others (Sec. 3.3)."""
+        carried over (ap_refresh_selection) on the others (Sec. 3.3).  The predictor state then either
+        advances on every step anyway, or - from skip_predictor_from steps between selections on - the
+        predictor is left out on the steps in between and evaluates the full tile when it is needed
+        (one full tile costs about as much as a dozen advances)."""
         self.w = w
         self.refresh_every = refresh_every
+        self.skip_predictor_from = 12
         self.steps_done = 0
         self.incremental = incremental
         self.rebase_every = rebase_every
@@ -83,11 +87,19 @@ class DecodeRun:
         return (self.steps_done % self.refresh_every == 0 or self.nb(t - 1) <= k < self.nb(t)
                 or self.nb(t) <= k)
 
+    def _step_mode(self, t, selects):
+        """Predictor mode of this step; AP_PRED_SKIP on steps that carry the selection over under a long interval."""
+        if not selects and self.refresh_every >= self.skip_predictor_from:
+            return AP_PRED_SKIP
+        return self._pred_mode(t)
+
     def step_unfused(self, q, K, V, t, calibrate=False):
         nb = self.nb(t)
-        mode = self._pred_mode(t)
         selects = self.selects_now(t)
-        if self.incremental:
+        mode = self._step_mode(t, selects)
+        if mode == AP_PRED_SKIP:
+            pass
+        elif self.incremental:
             self.ctx.predict_incremental(self.hist, self.n_pushed, nb, self.nb(max(t - 1, 1)), mode, self.pstate,
                                          self.pred, self.ws)
             self.state_n, self.state_t = self.n_pushed, t
@@ -106,11 +118,12 @@ class DecodeRun:
         return mode
 
     def step(self, q, K, V, t, calibrate=False):
-        mode = self._pred_mode(t)
-        flag = 0 if self.selects_now(t) else AP_STEP_REUSE_SELECTION
+        selects = self.selects_now(t)
+        mode = self._step_mode(t, selects)
+        flag = 0 if selects else AP_STEP_REUSE_SELECTION
         self.ctx.step(self.hist, self.n_pushed, q, K, V, t, self.out, self.idx, self.cnt, self.pred,
                       self.pstate if self.incremental else None, mode | flag, self.ws)
-        if self.incremental:
+        if self.incremental and mode != AP_PRED_SKIP:
             self.state_n, self.state_t = self.n_pushed, t
         if calibrate:
             self.ctx.calibrate(q, K, t, self.row, self.ws)
