@@ -29,11 +29,13 @@ __device__ __forceinline__ uint32_t score_key(float x) {
 
 // Adds one to hist[bin] for every lane with `active`.  Predicted scores of neighbouring blocks are close,
 // so most lanes of a wave share a bin and per-lane LDS atomics would serialise on it: the two most common
-// leading bins are counted with a ballot and added once per wave, the rest fall back to single adds.
+// leading bins are counted with a ballot and added once per wave (ROUNDS of them), the rest fall back to
+// single adds.
+template <int ROUNDS>
 __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool active) {
   const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
-  for (int round = 0; round < 2; ++round) {
+  for (int round = 0; round < ROUNDS; ++round) {
     const unsigned long long live = __ballot(active);
     if (live == 0) return;
     const int leader = __ffsll((long long)live) - 1;      // wave-uniform: one v_readlane instead of a shuffle
@@ -97,7 +99,10 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
         const int j = lo + i * kSelThreads + tid;
         const uint32_t key = key_at(i, j);
         const bool match = j < hi && ((shift == 24) || ((key >> (shift + 8)) == prefix));
-        hist_add(hist, (key >> shift) & 255u, match);
+        // The two leading bytes are shared by most scores; the two trailing ones spread over the bins, where one
+        // aggregation round (it still collapses a row of equal scores) and plain adds for the rest cost less.
+        if (shift >= 16) hist_add<2>(hist, (key >> shift) & 255u, match);
+        else hist_add<1>(hist, (key >> shift) & 255u, match);
       }
       __syncthreads();
       // Suffix sums over bins, highest bin first: lane l owns bins 255 - 4l .. 252 - 4l.
