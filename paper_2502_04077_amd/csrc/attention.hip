@@ -76,14 +76,16 @@ __global__ __launch_bounds__(kAttnThreads) void calibrate_kernel(CalibArgs a) {
   float* s_m = s_bmp + G * a.chunk_blocks;
   float* s_l = s_m + G;
   int* s_phys = reinterpret_cast<int*>(s_l + G);   // [chunk_blocks] place of each block of the chunk in K
+  float* s_stage = smem + (((reinterpret_cast<float*>(s_phys + a.chunk_blocks) - smem) + 3) & ~3);
 
   for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
     s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + c0 + j], 0), a.n_phys - 1) : c0 + j;
   __syncthreads();
   const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
   const T* K_inst = static_cast<const T*>(a.K) + (a.table ? 0 : (size_t)inst * a.t_cap * D);
-  qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; },
-                     [&](int jb) { return s_phys[jb]; }, s_p, ld);
+  constexpr bool kStage = std::is_same<T, bf16_t>::value;
+  qk_logits<T, D, G, kStage>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; },
+                     [&](int jb) { return s_phys[jb]; }, s_p, ld, s_stage);
   __syncthreads();
   softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
   for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
@@ -146,7 +148,8 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
 
 template <typename T, int D, int G>
 hipError_t run_calib(const Shape& s, CalibArgs a, hipStream_t st) {
-  const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G + a.chunk_blocks);
+  const size_t stage = std::is_same<T, bf16_t>::value ? 4 + k_stage_floats<D>() : 0;     // + alignment slack
+  const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G + a.chunk_blocks + stage);
   calibrate_kernel<T, D, G><<<dim3(a.n_chunks, s.n_inst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -94,9 +94,19 @@ template <typename T, int D, int G> struct Geom {
 // contiguous bytes over the four steps and the four groups together cover the whole 256-byte row.
 // D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so lanes with head < G hold the logits.
 // fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
-template <typename T, int D, int G, class BlockOf, class PhysOf>
+// STAGE (bf16 only): K rows are fetched whole - LPT adjacent lanes read one row with non-temporal loads, as V rows
+// are - and pass through a wave-private LDS tile from which the MFMA operand layout is read.  A plain streaming
+// read of this machine is 14 % faster with non-temporal loads, but only if an instruction covers whole 128-byte
+// lines: the direct operand layout gives a row 64 bytes per instruction, and non-temporal loads of part of a line
+// fetch it again for the other part.  It costs kAttnWaves * 16 rows of LDS, so only the kernel with LDS to spare
+// (calibration) uses it.
+constexpr int kStageRowPad = 16;   // bytes added to a staged K row so that 16 rows spread over the LDS banks
+template <int D> constexpr int k_stage_floats() { return kAttnWaves * kGroupTokens * (D * 2 + kStageRowPad) / 4; }
+
+template <typename T, int D, int G, bool STAGE = false, class BlockOf, class PhysOf>
 __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
-                                          int t_cur, int ntok, BlockOf block_of, PhysOf phys_of, float* s_p, int ld) {
+                                          int t_cur, int ntok, BlockOf block_of, PhysOf phys_of, float* s_p, int ld,
+                                          float* s_stage = nullptr) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const float scale = rsqrtf((float)D);
@@ -111,26 +121,8 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
       if (row < G) w = *reinterpret_cast<const uint4*>(q_inst + (size_t)row * D + g * (D / 4) + s * 8);
       qb[s] = __builtin_bit_cast(bf16x8, w);
     }
-    auto load_group = [&](int grp, uint4 (&kw)[KS]) __attribute__((always_inline)) {
-      const int tau = grp * kGroupTokens + row;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
-      if (tau < ntok) {
-        const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
-        const T* src = K_inst + (size_t)ptok * D + g * (D / 4);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kw[s] = *reinterpret_cast<const uint4*>(src + s * 8);
-      }
-    };
-    uint4 cur[KS], nxt[KS];
-    if (wave < ngroups) load_group(wave, cur);
-    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
-      const bool more = grp + kAttnWaves < ngroups;
-      if (more) load_group(grp + kAttnWaves, nxt);
-      float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[s]), qb[s], acc, 0, 0, 0);
+    // Logits of one 16-token group: lane (head = row, tokens 4 g .. 4 g + 3) holds them after the MFMAs.
+    auto store_logits = [&](int grp, const float4v& acc) __attribute__((always_inline)) {
       const int tau0 = grp * kGroupTokens + 4 * g;       // four tokens of one block (b is a multiple of 8)
       if (row < G && tau0 < ntok) {
         const int gtok0 = block_of(tau0 >> log2b) * b + (tau0 & (b - 1));
@@ -141,9 +133,64 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
         o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
         *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
       }
-      if (more) {
+    };
+    if constexpr (STAGE) {
+      constexpr int LPT = D / 8, TPI = kWave / LPT, NLK = kGroupTokens / TPI, RS = D * 2 + kStageRowPad;
+      char* stage = reinterpret_cast<char*>(s_stage) + wave * kGroupTokens * RS;
+      auto load_group = [&](int grp, uint4 (&v)[NLK]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < KS; ++s) cur[s] = nxt[s];
+        for (int i = 0; i < NLK; ++i) {
+          const int tau = grp * kGroupTokens + i * TPI + lane / LPT;
+          v[i] = make_uint4(0, 0, 0, 0);
+          if (tau < ntok) {
+            const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
+            v[i] = ld_stream(K_inst + (size_t)ptok * D + (lane % LPT) * 8);
+          }
+        }
+      };
+      uint4 cur[NLK];
+      if (wave < ngroups) load_group(wave, cur);
+      for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+#pragma unroll
+        for (int i = 0; i < NLK; ++i)
+          *reinterpret_cast<uint4*>(stage + (i * TPI + lane / LPT) * RS + (lane % LPT) * 16) = cur[i];
+        asm volatile("" ::: "memory");                   // a wave's LDS accesses stay in order; so must the compiler
+        if (grp + kAttnWaves < ngroups) load_group(grp + kAttnWaves, cur);
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const uint4 kw = *reinterpret_cast<const uint4*>(stage + row * RS + (g * (D / 4) + s * 8) * 2);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kw), qb[s], acc, 0, 0, 0);
+        }
+        asm volatile("" ::: "memory");                   // the next group overwrites the tile read above
+        store_logits(grp, acc);
+      }
+    } else {
+      auto load_group = [&](int grp, uint4 (&kw)[KS]) __attribute__((always_inline)) {
+        const int tau = grp * kGroupTokens + row;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
+        if (tau < ntok) {
+          const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
+          const T* src = K_inst + (size_t)ptok * D + g * (D / 4);
+#pragma unroll
+          for (int s = 0; s < KS; ++s) kw[s] = *reinterpret_cast<const uint4*>(src + s * 8);
+        }
+      };
+      uint4 cur[KS], nxt[KS];
+      if (wave < ngroups) load_group(wave, cur);
+      for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+        const bool more = grp + kAttnWaves < ngroups;
+        if (more) load_group(grp + kAttnWaves, nxt);
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[s]), qb[s], acc, 0, 0, 0);
+        store_logits(grp, acc);
+        if (more) {
+#pragma unroll
+          for (int s = 0; s < KS; ++s) cur[s] = nxt[s];
+        }
       }
     }
   } else {
