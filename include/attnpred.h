@@ -243,7 +243,7 @@ int ap_offload_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, c
                     void* compute_stream, void* copy_stream);
 
 /* Measurement aids (no part of Algorithm 1): a streaming read of `bytes` bytes (multiple of 16) of
- * device memory with 16-byte loads per lane, and a plain copy.  They give the read bandwidth the
+ * device memory with 16-byte non-temporal loads per lane, and a plain copy.  They give the read bandwidth the
  * machine actually reaches, quoted beside the published peak, and a kernel of known traffic against
  * which hardware byte counters are scaled.
  *   sink  device, at least 16 * n_workgroups bytes (read: one checksum word per workgroup is xor-ed in)
