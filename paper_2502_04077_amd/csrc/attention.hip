@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kAttnThreads) void calibrate_kernel(CalibArgs a) {
   __syncthreads();
   const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
   const T* K_inst = static_cast<const T*>(a.K) + (a.table ? 0 : (size_t)inst * a.t_cap * D);
-  constexpr bool kStage = std::is_same<T, bf16_t>::value;
+  constexpr int kStage = std::is_same<T, bf16_t>::value ? kGroupTokens : 0;
   qk_logits<T, D, G, kStage>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; },
                      [&](int jb) { return s_phys[jb]; }, s_p, ld, s_stage);
   __syncthreads();

@@ -101,9 +101,11 @@ template <typename T, int D, int G> struct Geom {
 // fetch it again for the other part.  It costs kAttnWaves * 16 rows of LDS, so only the kernel with LDS to spare
 // (calibration) uses it.
 constexpr int kStageRowPad = 16;   // bytes added to a staged K row so that 16 rows spread over the LDS banks
-template <int D> constexpr int k_stage_floats() { return kAttnWaves * kGroupTokens * (D * 2 + kStageRowPad) / 4; }
+template <int D, int ROWS = kGroupTokens> constexpr int k_stage_floats() { return kAttnWaves * ROWS * (D * 2 + kStageRowPad) / 4; }
 
-template <typename T, int D, int G, bool STAGE = false, class BlockOf, class PhysOf>
+// STAGE = 0: operands straight from global memory; 16: a 16-row tile per wave; 8: an 8-row tile (two passes per
+// 16 tokens through an MFMA whose other eight rows repeat them), which fits where the output partials go later.
+template <typename T, int D, int G, int STAGE = 0, class BlockOf, class PhysOf>
 __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
                                           int t_cur, int ntok, BlockOf block_of, PhysOf phys_of, float* s_p, int ld,
                                           float* s_stage = nullptr) {
@@ -134,13 +136,16 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
         *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
       }
     };
-    if constexpr (STAGE) {
-      constexpr int LPT = D / 8, TPI = kWave / LPT, NLK = kGroupTokens / TPI, RS = D * 2 + kStageRowPad;
-      char* stage = reinterpret_cast<char*>(s_stage) + wave * kGroupTokens * RS;
-      auto load_group = [&](int grp, uint4 (&v)[NLK]) __attribute__((always_inline)) {
+    if constexpr (STAGE != 0) {
+      constexpr int ROWS = STAGE;                        // tokens per pass
+      constexpr int LPT = D / 8, TPI = kWave / LPT, NLK = ROWS / TPI, RS = D * 2 + kStageRowPad;
+      static_assert(NLK >= 1, "a pass is at least one load instruction");
+      char* stage = reinterpret_cast<char*>(s_stage) + wave * ROWS * RS;
+      const int npass = (ntok + ROWS - 1) / ROWS;
+      auto load_pass = [&](int ps, uint4 (&v)[NLK]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NLK; ++i) {
-          const int tau = grp * kGroupTokens + i * TPI + lane / LPT;
+          const int tau = ps * ROWS + i * TPI + lane / LPT;
           v[i] = make_uint4(0, 0, 0, 0);
           if (tau < ntok) {
             const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
@@ -149,21 +154,31 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
         }
       };
       uint4 cur[NLK];
-      if (wave < ngroups) load_group(wave, cur);
-      for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      if (wave < npass) load_pass(wave, cur);
+      for (int ps = wave; ps < npass; ps += kAttnWaves) {
 #pragma unroll
         for (int i = 0; i < NLK; ++i)
           *reinterpret_cast<uint4*>(stage + (i * TPI + lane / LPT) * RS + (lane % LPT) * 16) = cur[i];
         asm volatile("" ::: "memory");                   // a wave's LDS accesses stay in order; so must the compiler
-        if (grp + kAttnWaves < ngroups) load_group(grp + kAttnWaves, cur);
+        if (ps + kAttnWaves < npass) load_pass(ps + kAttnWaves, cur);
         float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-          const uint4 kw = *reinterpret_cast<const uint4*>(stage + row * RS + (g * (D / 4) + s * 8) * 2);
+          const uint4 kw = *reinterpret_cast<const uint4*>(stage + (row & (ROWS - 1)) * RS + (g * (D / 4) + s * 8) * 2);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kw), qb[s], acc, 0, 0, 0);
         }
-        asm volatile("" ::: "memory");                   // the next group overwrites the tile read above
-        store_logits(grp, acc);
+        asm volatile("" ::: "memory");                   // the next pass overwrites the tile read above
+        // lane (head = row, tokens 4 g .. 4 g + 3 of the pass); with 8 rows only g < 2 holds tokens
+        const int tau0 = ps * ROWS + 4 * g;
+        if (row < G && 4 * g < ROWS && tau0 < ntok) {
+          const int gtok0 = block_of(tau0 >> log2b) * b + (tau0 & (b - 1));
+          float4 o;
+          o.x = gtok0 + 0 < t_cur ? acc[0] * scale : -INFINITY;
+          o.y = gtok0 + 1 < t_cur ? acc[1] * scale : -INFINITY;
+          o.z = gtok0 + 2 < t_cur ? acc[2] * scale : -INFINITY;
+          o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
+          *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
+        }
       }
     } else {
       auto load_group = [&](int grp, uint4 (&kw)[KS]) __attribute__((always_inline)) {
@@ -287,6 +302,12 @@ __device__ __forceinline__ void write_row(float* __restrict__ row, int nb_cap, c
   }
 }
 
+constexpr int kSparseStage = 8;
+// Floats of the region shared by the staged K tile (phase 1) and the per-wave output partials (after phase 3).
+template <int D, int G> constexpr int sparse_acc_floats() {
+  return kAttnWaves * G * D > k_stage_floats<D, kSparseStage>() ? kAttnWaves * G * D : k_stage_floats<D, kSparseStage>();
+}
+
 struct SparseArgs {
   const void* q; const void* K; const void* V;
   const int32_t* idx; const int32_t* cnt;
@@ -317,7 +338,7 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 
   float* s_p = smem;                                   // [G][ld]
   float* s_acc = s_p + G * ld;                         // [waves][G][D]
-  float* s_bmp = s_acc + kAttnWaves * G * D;           // [G][nblk_cap]
+  float* s_bmp = s_acc + sparse_acc_floats<D, G>();    // [G][nblk_cap]
   float* s_rowval = s_bmp + G * nblk_cap;              // [nblk_cap]
   float* s_m = s_rowval + nblk_cap;                    // [G]
   float* s_l = s_m + G;                                // [G]
@@ -344,8 +365,9 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
 
   if (nblk > 0) {
-    qk_logits<T, D, G>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; },
-                       [&](int jb) { return s_phys[jb]; }, s_p, ld);
+    // (the staged K tile lives where the waves' output partials go after phase 3)
+    qk_logits<T, D, G, kSparseStage>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; },
+                       [&](int jb) { return s_phys[jb]; }, s_p, ld, s_acc);
     __syncthreads();
     softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
 
@@ -435,7 +457,7 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 
 // LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens.
 template <int D, int G> inline size_t sparse_lds_floats(int nblk_cap, int b) {
-  return (size_t)G * nblk_cap * b + kAttnWaves * G * D + (size_t)G * nblk_cap + nblk_cap + 2 * G + 2 * nblk_cap;
+  return (size_t)G * nblk_cap * b + sparse_acc_floats<D, G>() + (size_t)G * nblk_cap + nblk_cap + 2 * G + 2 * nblk_cap;
 }
 
 }  // namespace
