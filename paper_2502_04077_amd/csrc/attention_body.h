@@ -88,27 +88,26 @@ template <typename T, int D, int G> struct Geom {
 //
 // bf16: the g x d by d x 16-token contraction runs on v_mfma_f32_16x16x32_bf16 (A = 16 K rows, B = q^T
 // padded to 16 columns, fp32 accumulate); with VALU dot products plus cross-lane sums the kernel spends
-// two thirds of its issue slots on arithmetic and cannot keep HBM busy.  Lane l supplies token l % 16
-// straight from global memory.  The order of the contraction index is free as long as A and B agree, so
-// lane group g = l / 16 takes dims g d/4 .. (g+1) d/4 - 1, eight per K-step: every lane reads 64
-// contiguous bytes over the four steps and the four groups together cover the whole 256-byte row.
-// D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so lanes with head < G hold the logits.
+// two thirds of its issue slots on arithmetic and cannot keep HBM busy.  In the operand layout lane l supplies
+// token l % 16 and, the order of the contraction index being free as long as A and B agree, dims
+// (l / 16) d/4 .. + d/4 - 1, eight per K-step.  D comes back as lane (head = l % 16, 4 (l / 16) + v = token), so
+// lanes with head < G hold the logits.
+// The K rows do not come from global memory in that layout (a row would get 64 bytes per load instruction):
+// they are fetched whole - LPT adjacent lanes read one row with non-temporal loads, as V rows are - and pass
+// through a wave-private LDS tile of STAGE rows from which the operand layout is read.  A plain streaming read
+// of this machine is 14 % faster with non-temporal loads, but only if an instruction covers whole 128-byte lines;
+// a non-temporal load of part of a line fetches the line again for the other part.
+//   STAGE = 16  one tile per 16-token group (calibration, which has the LDS to spare)
+//   STAGE = 8   an 8-row tile, two passes per 16 tokens through an MFMA whose other eight rows repeat the tile:
+//               it fits into the region that holds the output partials later (sparse decode)
 // fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
-// STAGE (bf16 only): K rows are fetched whole - LPT adjacent lanes read one row with non-temporal loads, as V rows
-// are - and pass through a wave-private LDS tile from which the MFMA operand layout is read.  A plain streaming
-// read of this machine is 14 % faster with non-temporal loads, but only if an instruction covers whole 128-byte
-// lines: the direct operand layout gives a row 64 bytes per instruction, and non-temporal loads of part of a line
-// fetch it again for the other part.  It costs kAttnWaves * 16 rows of LDS, so only the kernel with LDS to spare
-// (calibration) uses it.
 constexpr int kStageRowPad = 16;   // bytes added to a staged K row so that 16 rows spread over the LDS banks
 template <int D, int ROWS = kGroupTokens> constexpr int k_stage_floats() { return kAttnWaves * ROWS * (D * 2 + kStageRowPad) / 4; }
 
-// STAGE = 0: operands straight from global memory; 16: a 16-row tile per wave; 8: an 8-row tile (two passes per
-// 16 tokens through an MFMA whose other eight rows repeat them), which fits where the output partials go later.
-template <typename T, int D, int G, int STAGE = 0, class BlockOf, class PhysOf>
+template <typename T, int D, int G, int STAGE, class BlockOf, class PhysOf>
 __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
                                           int t_cur, int ntok, BlockOf block_of, PhysOf phys_of, float* s_p, int ld,
-                                          float* s_stage = nullptr) {
+                                          float* s_stage) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const float scale = rsqrtf((float)D);
@@ -123,20 +122,8 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
       if (row < G) w = *reinterpret_cast<const uint4*>(q_inst + (size_t)row * D + g * (D / 4) + s * 8);
       qb[s] = __builtin_bit_cast(bf16x8, w);
     }
-    // Logits of one 16-token group: lane (head = row, tokens 4 g .. 4 g + 3) holds them after the MFMAs.
-    auto store_logits = [&](int grp, const float4v& acc) __attribute__((always_inline)) {
-      const int tau0 = grp * kGroupTokens + 4 * g;       // four tokens of one block (b is a multiple of 8)
-      if (row < G && tau0 < ntok) {
-        const int gtok0 = block_of(tau0 >> log2b) * b + (tau0 & (b - 1));
-        float4 o;
-        o.x = gtok0 + 0 < t_cur ? acc[0] * scale : -INFINITY;
-        o.y = gtok0 + 1 < t_cur ? acc[1] * scale : -INFINITY;
-        o.z = gtok0 + 2 < t_cur ? acc[2] * scale : -INFINITY;
-        o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
-        *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
-      }
-    };
-    if constexpr (STAGE != 0) {
+    {
+      static_assert(STAGE == 8 || STAGE == 16, "bf16 K rows go through a staged tile of 8 or 16 rows");
       constexpr int ROWS = STAGE;                        // tokens per pass
       constexpr int LPT = D / 8, TPI = kWave / LPT, NLK = ROWS / TPI, RS = D * 2 + kStageRowPad;
       static_assert(NLK >= 1, "a pass is at least one load instruction");
@@ -178,33 +165,6 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
           o.z = gtok0 + 2 < t_cur ? acc[2] * scale : -INFINITY;
           o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
           *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
-        }
-      }
-    } else {
-      auto load_group = [&](int grp, uint4 (&kw)[KS]) __attribute__((always_inline)) {
-        const int tau = grp * kGroupTokens + row;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) kw[s] = make_uint4(0, 0, 0, 0);
-        if (tau < ntok) {
-          const int ptok = phys_of(tau >> log2b) * b + (tau & (b - 1));
-          const T* src = K_inst + (size_t)ptok * D + g * (D / 4);
-#pragma unroll
-          for (int s = 0; s < KS; ++s) kw[s] = *reinterpret_cast<const uint4*>(src + s * 8);
-        }
-      };
-      uint4 cur[KS], nxt[KS];
-      if (wave < ngroups) load_group(wave, cur);
-      for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
-        const bool more = grp + kAttnWaves < ngroups;
-        if (more) load_group(grp + kAttnWaves, nxt);
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur[s]), qb[s], acc, 0, 0, 0);
-        store_logits(grp, acc);
-        if (more) {
-#pragma unroll
-          for (int s = 0; s < KS; ++s) cur[s] = nxt[s];
         }
       }
     }
