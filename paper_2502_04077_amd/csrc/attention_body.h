@@ -140,14 +140,14 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
           }
         }
       };
-      uint4 cur[NLK];
-      if (wave < npass) load_pass(wave, cur);
-      for (int ps = wave; ps < npass; ps += kAttnWaves) {
+      // One pass: stage the fetched rows, refill the registers with pass `refill` (two passes of this wave ahead),
+      // contract, store the logits.
+      auto do_pass = [&](int ps, uint4 (&v)[NLK], int refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NLK; ++i)
-          *reinterpret_cast<uint4*>(stage + (i * TPI + lane / LPT) * RS + (lane % LPT) * 16) = cur[i];
+          *reinterpret_cast<uint4*>(stage + (i * TPI + lane / LPT) * RS + (lane % LPT) * 16) = v[i];
         asm volatile("" ::: "memory");                   // a wave's LDS accesses stay in order; so must the compiler
-        if (ps + kAttnWaves < npass) load_pass(ps + kAttnWaves, cur);
+        if (refill < npass) load_pass(refill, v);
         float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -166,6 +166,13 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
           o.w = gtok0 + 3 < t_cur ? acc[3] * scale : -INFINITY;
           *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
         }
+      };
+      uint4 va[NLK], vb[NLK];                            // rows of this wave's next two passes
+      if (wave < npass) load_pass(wave, va);
+      if (wave + kAttnWaves < npass) load_pass(wave + kAttnWaves, vb);
+      for (int ps = wave; ps < npass; ps += 2 * kAttnWaves) {
+        do_pass(ps, va, ps + 2 * kAttnWaves);
+        if (ps + kAttnWaves < npass) do_pass(ps + kAttnWaves, vb, ps + 3 * kAttnWaves);
       }
     }
   } else {
