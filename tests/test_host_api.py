@@ -87,6 +87,19 @@ def test_null_and_misaligned_pointers_are_refused_before_any_launch():
     assert lib.ap_predict_incremental(h, ok, 0, 100, 100, 9, ok, ok, ok, None) == -6
     assert lib.ap_set_weights(h, ok, 3, None) == -1                   # wrong blob length
     assert lib.ap_stream_read(None, 64, ok, 1, None) == -1
+    # the calls of the widened rows stop on the host as well
+    assert lib.ap_refresh_selection(h, 10, 5, ok, ok, None) == -3     # nb_prev > nb_cur
+    assert lib.ap_refresh_selection(h, 5, 10, None, ok, None) == -1
+    assert lib.ap_prefetch_state_bytes(h) == 8 * (3 * 64 + 4) * 4    # n_inst x (3k + 4) int32
+    assert lib.ap_prefetch_blocks(h, ok, ok, 10, 0, ok, ok, ok, ok, ok, ok, None) == -3
+    assert lib.ap_prefetch_blocks(h, ok, ok, 10, 5, ok, ok, ok, ok, ok, None, None) == -1
+    assert lib.ap_prefetch_blocks(h, ok, ok, 10, 5, ok, ok, ok, ok, ok, ok, None) == -1   # not device-readable memory
+    assert lib.ap_append_kv(h, ok, ok, -1, ok, ok, ok, ok, None) == -3
+    assert lib.ap_append_kv(h, ok, ok + 2, 3, ok, ok, ok, ok, None) == -2
+    assert lib.ap_offload_begin(h, ok, 0, ok, ok, 5, ok, ok, ok, ok, ok, ok, ok, ok, ok, None, None) == -6
+    assert lib.ap_offload_step(h, ok, 0, ok, ok, ok, ok, ok, 5, 0, ok, ok, ok, ok, ok, 1, ok, ok, ok, ok, ok, ok,
+                               None, None) == -6
+    assert lib.ap_step(h, ok, 0, ok, ok, ok, 5, ok, ok, ok, ok, ok, 3, ok, None) == -6
     assert lib.ap_destroy(h) == 0
     assert lib.ap_destroy(None) == -1
     for code in range(0, -8, -1):
