@@ -8,7 +8,7 @@ template <int KPT, int NT>
 __global__ __launch_bounds__(NT) void select_topk_kernel(const float* __restrict__ pred, int nb_cap, int nb_cur, int k,
                                                          int n_sink, int n_local, int inst0,
                                                          int32_t* __restrict__ idx, int32_t* __restrict__ cnt) {
-  __shared__ __align__(16) uint32_t s_mem[sel_scratch_words<NT>()];
+  __shared__ uint32_t s_mem[sel_scratch_words<NT>()];
   const int inst = inst0 + blockIdx.x;
   select_topk_body<KPT, NT>(pred + (size_t)inst * nb_cap, nb_cur, k, n_sink, n_local, idx + (size_t)inst * k,
                             cnt + inst, s_mem);

@@ -1,7 +1,7 @@
 // Top-K block selection (Algorithm 1 step 5) with forced sink / local blocks (Sec. 4.1).
 //
 // One workgroup per instance.  Scores are mapped to order-preserving 32-bit keys; a 4-pass
-// radix select (8 bits per pass, histogram in LDS, one barrier per pass) finds the key T of the k_mid-th largest score
+// radix select (8 bits per pass, histogram in LDS) finds the key T of the k_mid-th largest score
 // and how many scores equal to T are still needed.  A final ordered sweep keeps every block with
 // key > T and the first `need` blocks with key == T, compacting in index order, so the output is
 // ascending and equal scores go to the lower index.  Integer work only: the result is exact.
@@ -17,9 +17,7 @@ namespace {
 constexpr int kSelThreads = 256;           // workgroup size of the common variant
 constexpr int kSelThreadsWide = 1024;      // few instances, long rows: more threads per instance
 constexpr int kSelBins = 256;              // radix of one pass; the first kSelBins threads own one bin each
-// LDS words: three histograms (the one in use, the one being cleared for the next pass, the one waves may still
-// be reading) and two sets of per-wave (greater, equal) counts for the final sweep.
-template <int NT> constexpr int sel_scratch_words() { return 3 * kSelBins + 4 * (NT / kWave); }
+template <int NT> constexpr int sel_scratch_words() { return kSelBins + 3 * (NT / kWave) + 4; }
 
 __device__ __forceinline__ uint32_t score_key(float x) {
   uint32_t u = __float_as_uint(x);
@@ -29,17 +27,15 @@ __device__ __forceinline__ uint32_t score_key(float x) {
 
 // Adds one to hist[bin] for every lane with `active`.  Predicted scores of neighbouring blocks are close,
 // so most lanes of a wave share a bin and per-lane LDS atomics would serialise on it: the two most common
-// leading bins are counted with a ballot and added once per wave (ROUNDS of them), the rest fall back to
-// single adds.
-template <int ROUNDS>
+// leading bins are counted with a ballot and added once per wave, the rest fall back to single adds.
 __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool active) {
   const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
-  for (int round = 0; round < ROUNDS; ++round) {
+  for (int round = 0; round < 2; ++round) {
     const unsigned long long live = __ballot(active);
     if (live == 0) return;
-    const int leader = __ffsll((long long)live) - 1;      // wave-uniform: one v_readlane instead of a shuffle
-    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+    const int leader = __ffsll((long long)live) - 1;
+    const uint32_t b0 = (uint32_t)__shfl((int)bin, leader, kWave);
     const unsigned long long same = __ballot(active && bin == b0);
     if (lane == leader) atomicAdd(&hist[b0], (uint32_t)__popcll(same));
     if (bin == b0) active = false;
@@ -55,8 +51,12 @@ template <int KPT, int NT>   // KPT: keys per thread held in registers; 0 = re-r
 __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, int nb_cur, int k, int n_sink, int n_local,
                                         int32_t* __restrict__ out, int32_t* __restrict__ cnt_out, uint32_t* s_mem) {
   constexpr int kSelThreads = NT, kSelWaves = NT / kWave;
-  uint32_t* s_hist = s_mem;                     // [3][kSelBins]
-  uint32_t* s_cnt = s_mem + 3 * kSelBins;       // [2][greater | equal][kSelWaves]
+  uint32_t* s_hist = s_mem;                     // [kSelBins]
+  uint32_t* s_wsum = s_mem + kSelBins;          // [kSelWaves]
+  uint32_t* s_wgt = s_wsum + kSelWaves;         // [kSelWaves]
+  uint32_t* s_weq = s_wgt + kSelWaves;          // [kSelWaves]
+  uint32_t& s_bin = s_mem[kSelBins + 3 * kSelWaves];
+  uint32_t& s_above = s_mem[kSelBins + 3 * kSelWaves + 1];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
   if (nb_cur <= k) {                                    // everything fits the budget
@@ -86,56 +86,47 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
   uint32_t prefix = 0;                                  // high bits of T found so far
   uint32_t need = (uint32_t)k_mid;                      // still to take among keys matching prefix
   if (k_mid > 0) {
-    if (tid < kSelBins) s_hist[tid] = 0;
-    __syncthreads();
-    int pass = 0;
-    for (int shift = 24; shift >= 0; shift -= 8, ++pass) {
-      // One barrier per pass: the histogram of the next pass is cleared here (its last readers finished two
-      // passes ago), and every wave scans all bins by itself instead of sharing partial sums.
-      uint32_t* hist = s_hist + (pass % 3) * kSelBins;
-      if (tid < kSelBins) s_hist[((pass + 1) % 3) * kSelBins + tid] = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < kSelBins) s_hist[tid] = 0;
+      __syncthreads();
 #pragma unroll NK
       for (int i = 0; i < n_iter; ++i) {                   // uniform trip count: ballots need every lane
         const int j = lo + i * kSelThreads + tid;
         const uint32_t key = key_at(i, j);
         const bool match = j < hi && ((shift == 24) || ((key >> (shift + 8)) == prefix));
-        // The two leading bytes are shared by most scores; the two trailing ones spread over the bins, where one
-        // aggregation round (it still collapses a row of equal scores) and plain adds for the rest cost less.
-        if (shift >= 16) hist_add<2>(hist, (key >> shift) & 255u, match);
-        else hist_add<1>(hist, (key >> shift) & 255u, match);
+        hist_add(s_hist, (key >> shift) & 255u, match);
       }
       __syncthreads();
-      // Suffix sums over bins, highest bin first: lane l owns bins 255 - 4l .. 252 - 4l.
-      const uint4 c4 = *reinterpret_cast<const uint4*>(hist + kSelBins - 4 - 4 * lane);
-      const uint32_t c[4] = {c4.w, c4.z, c4.y, c4.x};
-      const uint32_t mine = c[0] + c[1] + c[2] + c[3];
-      uint32_t incl = mine;
+      // Suffix sums over bins: thread r < kSelBins handles bin 255 - r, inclusive scan in that order
+      // (whole waves take or skip these branches).
+      uint32_t c = 0, incl = 0;
+      if (tid < kSelBins) {
+        c = s_hist[kSelBins - 1 - tid];
+        incl = c;
 #pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += up;
-      }
-      uint32_t running = incl - mine;                   // keys in bins above this lane's four
-      uint32_t found_bin = 0, found_above = 0;
-      bool found = false;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (!found && running < need && need <= running + c[i]) {
-          found = true;
-          found_bin = kSelBins - 1 - 4 * lane - i;
-          found_above = running;
+        for (int o = 1; o < kWave; o <<= 1) {
+          const uint32_t up = __shfl_up(incl, o, kWave);
+          if (lane >= o) incl += up;
         }
-        running += c[i];
+        if (lane == kWave - 1) s_wsum[wave] = incl;
       }
-      const int owner = __ffsll((long long)__ballot(found)) - 1;   // exactly one lane: 1 <= need <= matching keys
-      prefix = (prefix << 8) | (uint32_t)__builtin_amdgcn_readlane((int)found_bin, owner);
-      need -= (uint32_t)__builtin_amdgcn_readlane((int)found_above, owner);
+      __syncthreads();
+      if (tid < kSelBins) {
+        uint32_t base = 0;
+        for (int w = 0; w < wave; ++w) base += s_wsum[w];
+        incl += base;                                   // keys in bins >= 255 - tid
+        const uint32_t excl = incl - c;                 // keys in bins >  255 - tid
+        if (excl < need && need <= incl) { s_bin = kSelBins - 1 - tid; s_above = excl; }
+      }
+      __syncthreads();
+      prefix = (prefix << 8) | s_bin;
+      need -= s_above;
+      __syncthreads();
     }
   }
   const uint32_t T = prefix;
 
-  // Ordered sweep in chunks of one workgroup width; the per-wave counts alternate between two sets, so one
-  // barrier per chunk is enough.
+  // Ordered sweep in chunks of one workgroup width.
   uint32_t taken = 0;                                   // selected so far (all threads agree)
   uint32_t eq_seen = 0;                                 // keys == T seen so far
 #pragma unroll NK
@@ -150,8 +141,6 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
     }
     const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
     const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (kWave - lane));
-    uint32_t* s_wgt = s_cnt + (i & 1) * 2 * kSelWaves;
-    uint32_t* s_weq = s_wgt + kSelWaves;
     if (lane == 0) { s_wgt[wave] = __popcll(bgt); s_weq[wave] = __popcll(beq); }
     __syncthreads();
     uint32_t gt_before = __popcll(bgt & below), eq_before = __popcll(beq & below);
@@ -168,6 +157,7 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
     if (take) out[n_sink + taken + gt_before + eq_taken_before] = j;
     taken += gt_total + (min(eq_seen + eq_total, need) - min(eq_seen, need));
     eq_seen += eq_total;
+    __syncthreads();
   }
   for (int j = tid; j < n_sink; j += kSelThreads) out[j] = j;
   for (int j = tid; j < n_local; j += kSelThreads) out[k - n_local + j] = nb_cur - n_local + j;
