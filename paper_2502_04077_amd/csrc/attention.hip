@@ -137,7 +137,7 @@ int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 template <typename T, int D, int G>
 hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
-  const size_t lds = sizeof(float) * sparse_lds_floats<D, G>(nblk_cap, a.b);
+  const size_t lds = sizeof(float) * sparse_lds_floats<D, G>(nblk_cap, a.b, a.nb_cap);
   sparse_decode_kernel<T, D, G><<<dim3(a.n_split, ninst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.n_split == 1) return e;

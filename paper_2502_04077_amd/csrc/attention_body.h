@@ -41,9 +41,9 @@ __device__ __forceinline__ void unpack16(const uint4& w, float (&f)[8], bf16_t) 
   f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
 }
 
-// V rows are read once per call, a whole row per load instruction: 16-byte non-temporal loads keep them from
-// displacing data that is re-used from cache.  (K rows are read as two half-lines by consecutive MFMA
-// K-steps and are left to the cache: non-temporal K loads measured 9 % slower in the calibration kernel.)
+// V rows and bf16 K rows are read once per call, a whole row per load instruction (the K rows through a staged
+// tile, see qk_logits): 16-byte non-temporal loads, which stream faster than plain ones and keep the rows
+// from displacing data that is re-used from cache.
 template <typename T> __device__ __forceinline__ uint4 ld_stream(const T* p) {
   typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
@@ -125,6 +125,7 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
     {
       static_assert(STAGE == 8 || STAGE == 16, "bf16 K rows go through a staged tile of 8 or 16 rows");
       constexpr int ROWS = STAGE;                        // tokens per pass
+      constexpr int NPRE = 2;                            // passes of a wave in flight (3, 4 and 6 measured the same)
       constexpr int LPT = D / 8, TPI = kWave / LPT, NLK = ROWS / TPI, RS = D * 2 + kStageRowPad;
       static_assert(NLK >= 1, "a pass is at least one load instruction");
       char* stage = reinterpret_cast<char*>(s_stage) + wave * ROWS * RS;
@@ -140,7 +141,7 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
           }
         }
       };
-      // One pass: stage the fetched rows, refill the registers with pass `refill` (two passes of this wave ahead),
+      // One pass: stage the fetched rows, refill the registers with pass `refill` (NPRE passes of this wave ahead),
       // contract, store the logits.
       auto do_pass = [&](int ps, uint4 (&v)[NLK], int refill) __attribute__((always_inline)) {
 #pragma unroll
@@ -167,12 +168,15 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
           *reinterpret_cast<float4*>(s_p + row * ld + tau0) = o;
         }
       };
-      uint4 va[NLK], vb[NLK];                            // rows of this wave's next two passes
-      if (wave < npass) load_pass(wave, va);
-      if (wave + kAttnWaves < npass) load_pass(wave + kAttnWaves, vb);
-      for (int ps = wave; ps < npass; ps += 2 * kAttnWaves) {
-        do_pass(ps, va, ps + 2 * kAttnWaves);
-        if (ps + kAttnWaves < npass) do_pass(ps + kAttnWaves, vb, ps + 3 * kAttnWaves);
+      // Rows of this wave's next NPRE passes wait in registers.
+      uint4 v[NPRE][NLK];
+#pragma unroll
+      for (int i = 0; i < NPRE; ++i)
+        if (wave + i * kAttnWaves < npass) load_pass(wave + i * kAttnWaves, v[i]);
+      for (int ps = wave; ps < npass; ps += NPRE * kAttnWaves) {
+#pragma unroll
+        for (int i = 0; i < NPRE; ++i)
+          if (ps + i * kAttnWaves < npass) do_pass(ps + i * kAttnWaves, v[i], ps + (i + NPRE) * kAttnWaves);
       }
     }
   } else {
@@ -225,32 +229,43 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
 }
 
 // Phase 2.  Leaves p in s_p, (M, L) in s_m / s_l, per (head, block) max p in s_bmp[h * nblk + jb].
+// One wave per head; a lane handles four consecutive tokens per 16-byte LDS access (ntok and ld are multiples
+// of the block size, hence of 4), so the b / 4 adjacent lanes of a block find its maximum with DPP moves.
 template <int G>
 __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int b, int nblk, float* s_m, float* s_l,
                                      float* s_bmp) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
+  const int nquad = ntok >> 2;
+  const int lanes_per_blk = b >> 2;                      // 2, 4, 8 or 16
+  const int blk_shift = __ffs(lanes_per_blk) - 1;
   for (int h = wave; h < G; h += kAttnWaves) {
+    float4* prow = reinterpret_cast<float4*>(s_p + (size_t)h * ld);
     float m = -INFINITY;
-    for (int tau = lane; tau < ntok; tau += kWave) m = fmaxf(m, s_p[h * ld + tau]);
+    for (int qd = lane; qd < nquad; qd += kWave) {
+      const float4 v = prow[qd];
+      m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+    }
     m = wave_max(m);
     float sum = 0.f;
-    for (int tau = lane; tau < ntok; tau += kWave) {
-      const float p = __expf(s_p[h * ld + tau] - m);
-      s_p[h * ld + tau] = p;
-      sum += p;
+    for (int q0 = 0; q0 < nquad; q0 += kWave) {          // uniform trip count: the DPP moves need every lane
+      const int qd = q0 + lane;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (qd < nquad) {
+        v = prow[qd];
+        v.x = __expf(v.x - m); v.y = __expf(v.y - m); v.z = __expf(v.z - m); v.w = __expf(v.w - m);
+        prow[qd] = v;
+      }
+      sum += (v.x + v.y) + (v.z + v.w);
+      float bm = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+      bm = fmaxf(bm, dpp_move<0xB1>(bm));                                   // quad_perm [1,0,3,2]
+      if (lanes_per_blk >= 4) bm = fmaxf(bm, dpp_move<0x4E>(bm));           // quad_perm [2,3,0,1]
+      if (lanes_per_blk >= 8) bm = fmaxf(bm, dpp_move<0x141>(bm));          // row_half_mirror
+      if (lanes_per_blk >= 16) bm = fmaxf(bm, dpp_move<0x140>(bm));         // row_mirror
+      if (qd < nquad && (lane & (lanes_per_blk - 1)) == 0) s_bmp[h * nblk + (qd >> blk_shift)] = bm;
     }
     sum = wave_sum(sum);
     if (lane == 0) { s_m[h] = m; s_l[h] = sum; }
-  }
-  __syncthreads();
-  for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
-    const int h = pair / nblk, jb = pair - h * nblk;
-    const int t0 = jb * b;
-    const int t1 = min(t0 + b, ntok);
-    float mx = 0.f;
-    for (int tau = t0; tau < t1; ++tau) mx = fmaxf(mx, s_p[h * ld + tau]);
-    s_bmp[pair] = mx;
   }
   __syncthreads();
 }
@@ -306,18 +321,45 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
   float* s_p = smem;                                   // [G][ld]
   float* s_acc = s_p + G * ld;                         // [waves][G][D]
   float* s_bmp = s_acc + sparse_acc_floats<D, G>();    // [G][nblk_cap]
-  float* s_rowval = s_bmp + G * nblk_cap;              // [nblk_cap]
-  float* s_m = s_rowval + nblk_cap;                    // [G]
+  float* s_m = s_bmp + G * nblk_cap;                   // [G]
   float* s_l = s_m + G;                                // [G]
   int* s_idx = reinterpret_cast<int*>(s_l + G);        // [nblk_cap] logical block of each list position
   int* s_phys = s_idx + nblk_cap;                      // [nblk_cap] its place in K / V
+  // For the pooled row, written whole by the workgroup that has the whole list: one bit per block (is it
+  // listed) and, per 32-block word, the number of listed blocks before it, so that a column finds its list
+  // position without a search.
+  uint32_t* s_listed = reinterpret_cast<uint32_t*>(s_phys + nblk_cap);   // [ceil(nb_cap / 32)]
+  int* s_rank = reinterpret_cast<int*>(s_listed) + (a.nb_cap + 31) / 32; // [ceil(nb_cap / 32)]
+  const int nwords = (a.nb_cap + 31) / 32;
+  const bool whole_row = a.n_split == 1;
 
+  if (whole_row) {
+    for (int w = threadIdx.x; w < nwords; w += kAttnThreads) s_listed[w] = 0u;
+    __syncthreads();
+  }
   for (int j = threadIdx.x; j < nblk; j += kAttnThreads) {
     const int blk = min(max(a.idx[(size_t)inst * a.k + j0 + j], 0), a.nb_cur - 1);
     s_idx[j] = blk;
     s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + blk], 0), a.n_phys - 1) : blk;
+    if (whole_row) atomicOr(&s_listed[blk >> 5], 1u << (blk & 31));
   }
   __syncthreads();
+  if (whole_row && wave == kAttnWaves - 1) {           // exclusive prefix sum of the words' bit counts
+    const int per_lane = (nwords + kWave - 1) / kWave;
+    const int w0 = lane * per_lane;
+    int mine = 0;
+    for (int i = 0; i < per_lane; ++i)
+      if (w0 + i < nwords) mine += __popc(s_listed[w0 + i]);
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += up;
+    }
+    int run = incl - mine;
+    for (int i = 0; i < per_lane; ++i)
+      if (w0 + i < nwords) { s_rank[w0 + i] = run; run += __popc(s_listed[w0 + i]); }
+  }                                                    // (read after the barriers that follow)
 
   // Contiguous cache: [n_inst][t_cap][d].  Paged cache: one pool [n_phys][b][d] for all instances.
   const size_t kv_off = a.table ? 0 : (size_t)inst * a.t_cap * D;
@@ -394,14 +436,18 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
       for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
       a.out[(size_t)inst * G * D + o] = v / s_l[o / D];
     }
-    for (int jb = threadIdx.x; jb < nblk; jb += kAttnThreads) {
+    // Pooled row: column j of a listed block gets the largest block maximum over the heads, the rest zero.
+    float* row = a.row + (size_t)inst * a.row_stride;
+    for (int j = threadIdx.x; j < a.nb_cap; j += kAttnThreads) {
+      const uint32_t word = s_listed[j >> 5];
       float mx = 0.f;
+      if ((word >> (j & 31)) & 1u) {
+        const int pos = min(s_rank[j >> 5] + __popc(word & ((1u << (j & 31)) - 1u)), nblk - 1);
 #pragma unroll
-      for (int h = 0; h < G; ++h) mx = fmaxf(mx, s_bmp[h * nblk + jb] / s_l[h]);
-      s_rowval[jb] = mx;
+        for (int h = 0; h < G; ++h) mx = fmaxf(mx, s_bmp[h * nblk + pos] / s_l[h]);
+      }
+      row[j] = mx;
     }
-    __syncthreads();
-    write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, nblk, [&](int pos) { return s_rowval[pos]; });
   } else {
     const size_t ps = (size_t)inst * a.n_split + split;
     for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
@@ -422,9 +468,10 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 }
 
 
-// LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens.
-template <int D, int G> inline size_t sparse_lds_floats(int nblk_cap, int b) {
-  return (size_t)G * nblk_cap * b + sparse_acc_floats<D, G>() + (size_t)G * nblk_cap + nblk_cap + 2 * G + 2 * nblk_cap;
+// LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens out of nb_cap.
+template <int D, int G> inline size_t sparse_lds_floats(int nblk_cap, int b, int nb_cap) {
+  return (size_t)G * nblk_cap * b + sparse_acc_floats<D, G>() + (size_t)G * nblk_cap + 2 * G + 2 * nblk_cap +
+         2 * (size_t)((nb_cap + 31) / 32);
 }
 
 }  // namespace
