@@ -380,19 +380,35 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     __syncthreads();
     softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
 
-    // Phase 3: acc += p * V, same token-to-lane mapping as phase 1.
+    // Phase 3: acc += p * V.  A lane group takes NL consecutive tokens of a 16-token group (they lie in one
+    // block, so one table lookup places them), load instruction i covers the i-th row of each of the TPI lane
+    // groups - whole 256-byte rows as before - and the NL probabilities of a head come in one LDS access.
     const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+    static_assert(NL == 2 || NL == 4 || NL == 8, "probabilities are fetched as 8- or 16-byte vectors");
     for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+      const int tau0 = grp * kGroupTokens + tslot * NL;   // ntok is a multiple of 8 >= NL: all NL tokens or none
+      const bool live = tau0 < ntok;
       uint4 vw[NL];
-      int tau_i[NL];
 #pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const int tau = grp * kGroupTokens + i * TPI + tslot;
-        tau_i[i] = tau < ntok ? tau : -1;
-        vw[i] = make_uint4(0, 0, 0, 0);
-        if (tau < ntok) {
-          const int ptok = s_phys[tau >> a.log2b] * a.b + (tau & (a.b - 1));
-          vw[i] = ld_stream(V_inst + (size_t)ptok * D + dpart * E);
+      for (int i = 0; i < NL; ++i) vw[i] = make_uint4(0, 0, 0, 0);
+      if (live) {
+        const int ptok0 = s_phys[tau0 >> a.log2b] * a.b + (tau0 & (a.b - 1));
+#pragma unroll
+        for (int i = 0; i < NL; ++i) vw[i] = ld_stream(V_inst + (size_t)(ptok0 + i) * D + dpart * E);
+      }
+      float pw[G][NL];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float* src = s_p + h * ld + tau0;
+        if constexpr (NL == 2) {
+          const float2 t = *reinterpret_cast<const float2*>(src);
+          pw[h][0] = t.x; pw[h][1] = t.y;
+        } else {
+#pragma unroll
+          for (int c = 0; c < NL / 4; ++c) {
+            const float4 t = *reinterpret_cast<const float4*>(src + 4 * c);
+            pw[h][4 * c] = t.x; pw[h][4 * c + 1] = t.y; pw[h][4 * c + 2] = t.z; pw[h][4 * c + 3] = t.w;
+          }
         }
       }
 #pragma unroll
@@ -401,7 +417,7 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
         unpack16(vw[i], vf, T{});
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-          const float p = tau_i[i] >= 0 ? s_p[h * ld + tau_i[i]] : 0.f;
+          const float p = live ? pw[h][i] : 0.f;
 #pragma unroll
           for (int e = 0; e < E; ++e) acc[h][e] = fmaf(p, vf[e], acc[h][e]);
         }
