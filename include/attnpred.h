@@ -156,6 +156,8 @@ int ap_refresh_selection(ap_ctx* ctx, int32_t nb_prev, int32_t nb_cur, int32_t* 
  *   q    device [n_inst][g][d]      kv dtype
  *   K,V  device [n_inst][t_cap][d]  kv dtype
  *   idx  ascending, in [0, ceil(t_cur/b)); out-of-range entries are clamped into it
+ *   cnt  entries of idx that count, clamped into [0, k]; any value is allowed (the selection calls
+ *        write min(k, nb_cur)); with cnt = 0 the instance's out and row are all zero
  *   out  device float [n_inst][g][d]
  *   row  device float [n_inst][nb_cap]: max over the group's heads and over the block's tokens of
  *        the sparse softmax probability for selected blocks, 0 for all others (up to nb_cap) */

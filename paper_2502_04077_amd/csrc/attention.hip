@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs
       s_scale[s * G + h] = sc;
       L += ml[(size_t)s * G * 2 + 1] * sc;
     }
-    const float invL = 1.f / L;
+    const float invL = L > 0.f ? 1.f / L : 0.f;          // an empty list gives a zero output
     for (int s = 0; s < a.n_split; ++s) s_scale[s * G + h] *= invL;
   }
   __syncthreads();

@@ -450,7 +450,8 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
       float v = 0.f;
 #pragma unroll
       for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
-      a.out[(size_t)inst * G * D + o] = v / s_l[o / D];
+      const float L = s_l[o / D];
+      a.out[(size_t)inst * G * D + o] = L > 0.f ? v / L : 0.f;      // an empty list gives a zero output
     }
     // Pooled row: column j of a listed block gets the largest block maximum over the heads, the rest zero.
     float* row = a.row + (size_t)inst * a.row_stride;

@@ -258,6 +258,48 @@ def test_sparse_decode_vs_oracle(name, kw, t_cur):
         assert np.all(row[i][unsel] == 0.0)
 
 
+@pytest.mark.parametrize("kw", [dict(kv_heads=6, g=4, head_dim=128, budget_tokens=512, t0=3000),
+                                dict(kv_heads=8, batch=130, g=4, head_dim=128, budget_tokens=256, t0=600)],
+                         ids=["split", "whole"])
+def test_sparse_decode_ragged_counts(kw):
+    """Lists shorter than the budget, one of them empty; the idx entries past cnt are garbage and must be ignored.
+    An empty list gives a zero output and a zero row."""
+    dev = _dev()
+    w = small("ragged", **kw)
+    run = _run(w, dev)
+    K, V = kv_cache(w, dev)
+    q = queries(w, 0, dev)
+    rng = np.random.default_rng(11)
+    t_cur = w.t0 - 3
+    nb, k = run.nb(t_cur), w.k_blocks
+    cnt = rng.integers(1, k + 1, size=w.n_inst).astype(np.int32)
+    cnt[0], cnt[1], cnt[2] = 0, 1, k - 1
+    idx = np.full((w.n_inst, k), 2**30, dtype=np.int32)
+    lists = []
+    for i in range(w.n_inst):
+        blk = np.sort(rng.choice(nb, size=cnt[i], replace=False))
+        lists.append(blk)
+        idx[i, :cnt[i]] = blk
+    run.idx.copy_(torch.from_numpy(idx).to(dev))
+    run.cnt.copy_(torch.from_numpy(cnt).to(dev))
+    run.row.fill_(9.0)
+    run.out.fill_(9.0)
+    run.ctx.sparse_decode(q, K, V, t_cur, run.idx, run.cnt, run.out, run.row, run.ws)
+    torch.cuda.synchronize()
+    out, row = run.out.cpu().numpy(), run.row.cpu().numpy()
+    assert np.all(out[0] == 0.0) and np.all(row[0] == 0.0)
+    for i in [1, 2, 3, w.n_inst // 2, w.n_inst - 1]:
+        ref_out, A = orc.sparse_attention(to_f64(q[i]), to_f64(K[i]), to_f64(V[i]), lists[i], w.block, t_cur)
+        for h in range(w.g):
+            assert_close(out[i, h], ref_out[h], f"ragged out inst {i} head {h}")
+        ref_row = np.zeros(run.nb_cap)
+        ref_row[:nb] = orc.pooled_row(A, w.block)
+        assert_close(row[i], ref_row, f"ragged row inst {i}")
+        unsel = np.ones(run.nb_cap, bool)
+        unsel[lists[i]] = False
+        assert np.all(row[i][unsel] == 0.0)
+
+
 def test_full_budget_is_dense_attention():
     """Budget >= context: the sparse path must reproduce dense attention (rows of the softmax sum to 1)."""
     dev = _dev()
