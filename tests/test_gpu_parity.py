@@ -371,7 +371,7 @@ def test_update_history_ring_is_a_fifo():
 
 
 # --------------------------------------------------------------------------------------------- whole steps
-def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks=(0, -1)):
+def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks=(0, -1), warm=True):
     """Runs decode steps on the GPU; at each step the oracle starts from the GPU's own history.
     Only the sampled instances are copied to the host."""
     run = _run(w, dev)
@@ -385,7 +385,7 @@ def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks
     Vc = {i: to_f64(V[i]) for i in sample}
     sel = torch.as_tensor(sample, device=dev)
     # history warm-up: the last H prefill steps, dense rows (appendix "Training Details")
-    for j in range(H):
+    for j in range(H if warm else 0):
         t = w.t0 - H + 1 + j
         q = queries(w, j - H, dev)
         run.warmup_calibrate(q, K, t)
@@ -461,6 +461,19 @@ def test_lockstep_small_bf16_block_boundary():
     w = small("grow", kv_heads=4, g=4, head_dim=128, t0=1020, budget_tokens=256, hist_len=16, steps=12, calib_every=4)
     st = lockstep(w, dev, w.steps, sample=[0, 3])
     print("grow lock-step:", st)
+
+
+@pytest.mark.parametrize("H,c1,c2", [(8, 8, 8), (4, 4, 4)])
+def test_lockstep_from_first_token(H, c1, c2):
+    """Decoding from an empty context: the first step sees one token and a history of zero rows (the rows that
+    are missing early on are zero rows, appendix "Training Details"); the tile grows from one block, and the
+    budget of four blocks starts to bind after 32 tokens."""
+    dev = _dev()
+    w = small("first", kv_heads=2, t0=0, block=8, hist_len=H, budget_tokens=32, n_sink=1, n_local=1, c1=c1, c2=c2,
+              steps=60, calib_every=7)
+    st = lockstep(w, dev, w.steps, sample=[0, 1], warm=False)
+    print("from-first-token lock-step:", st)
+    assert st["checked"] == 120
 
 
 def test_lockstep_many_instances():
