@@ -106,6 +106,8 @@ def test_select_topk_bit_exact(nb, k, ns, nl, mode, n_inst):
 @pytest.mark.parametrize("H,nb,c1,c2,pushed", [
     (16, 128, 4, 4, 16), (16, 131, 4, 4, 40), (64, 200, 8, 8, 64), (64, 70, 8, 8, 7), (13, 65, 8, 8, 100),
     (64, 130, 16, 32, 64), (5, 1, 4, 4, 9), (8, 63, 8, 8, 0),
+    # longest and shortest histories of the MFMA kernels
+    (256, 150, 8, 8, 300), (256, 90, 16, 32, 256), (6, 200, 8, 8, 10), (7, 130, 16, 32, 3),
 ])
 def test_predict_vs_oracle(H, nb, c1, c2, pushed):
     dev = _dev()
