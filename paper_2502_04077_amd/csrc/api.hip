@@ -90,7 +90,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
     // Dynamic LDS of the attention workgroup (sparse_lds_floats) and of the combine kernel must fit 64 KiB.
     const size_t nblk = s.n_split == 1 ? s.k : (s.k + s.n_split - 1) / s.n_split;
     const size_t partials = (size_t)ap::kAttnWaves * s.g * s.d, tile = (size_t)ap::kAttnWaves * 8 * (2 * s.d + 16) / 4;
-    const size_t attn = (size_t)s.g * nblk * s.b + (partials > tile ? partials : tile) + (size_t)s.g * nblk + 2 * nblk + 2 * s.g + 2 * (size_t)((s.nb_cap + 31) / 32);
+    const size_t attn = (size_t)s.g * nblk * s.b + (partials > tile ? partials : tile) + (size_t)s.g * nblk + 2 * nblk + 4 * s.g + 2 * (size_t)((s.nb_cap + 31) / 32);
     const size_t comb = (size_t)s.n_split * s.g + (size_t)s.k;
     if (attn * sizeof(float) > 65536 || comb * sizeof(float) > 65536) { delete ctx; return AP_ERR_UNSUPPORTED; }
   }

@@ -4,10 +4,10 @@
 namespace ap {
 namespace {
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(kAttnThreads) void sparse_decode_kernel(SparseArgs a) {
+template <typename T, int D, int G, int NW, bool PIECED>
+__global__ __launch_bounds__(NW * kWave) void sparse_decode_kernel(SparseArgs a) {
   extern __shared__ __align__(16) float smem[];
-  sparse_decode_body<T, D, G>(a, a.inst0 + blockIdx.y, blockIdx.x, smem);
+  sparse_decode_body<T, D, G, NW, PIECED>(a, a.inst0 + blockIdx.y, blockIdx.x, smem);
 }
 
 // Merges the splits of one instance: global (M, L) per head, normalised output, pooled row.
@@ -134,11 +134,41 @@ __global__ __launch_bounds__(kAttnThreads) void calibrate_finish_kernel(CalibArg
 
 int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 
+// Workgroups of kernel `fn` (NT threads, lds bytes of LDS) the device holds at once; 0 if it cannot be asked.
+template <class Fn> int resident_workgroups(Fn fn, int nt, size_t lds) {
+  int per_cu = 0, dev = 0;
+  hipDeviceProp_t prop;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, nt, lds) != hipSuccess ||
+      hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+    return 0;
+  return per_cu * prop.multiProcessorCount;
+}
+
 template <typename T, int D, int G>
 hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
-  const size_t lds = sizeof(float) * sparse_lds_floats<D, G>(nblk_cap, a.b, a.nb_cap);
-  sparse_decode_kernel<T, D, G><<<dim3(a.n_split, ninst), kAttnThreads, lds, st>>>(a);
+  a.piece_blocks = nblk_cap;
+  const size_t lds = sizeof(float) * sparse_lds_floats<D, G, kAttnWaves>(nblk_cap, nblk_cap, a.b, a.nb_cap);
+  // More instances than the chip holds four-wave workgroups: the launch runs in rounds, the last one part
+  // empty, and every round pays its start-up and drain.  Two-wave workgroups that keep the probabilities of
+  // kNarrowPieceTokens tokens at a time are small enough for more of them to be resident; they are used when
+  // that saves a round.
+  if (a.n_split == 1 && nblk_cap * a.b > kNarrowPieceTokens) {
+    const int pb_n = kNarrowPieceTokens / a.b;
+    const size_t lds_n = sizeof(float) * sparse_lds_floats<D, G, kNarrowWaves>(nblk_cap, pb_n, a.b, a.nb_cap);
+    if (s.sparse_slots < 0) {
+      s.sparse_slots = resident_workgroups(sparse_decode_kernel<T, D, G, kAttnWaves, false>, kAttnThreads, lds);
+      s.sparse_slots_narrow = resident_workgroups(sparse_decode_kernel<T, D, G, kNarrowWaves, true>,
+                                                  kNarrowWaves * kWave, lds_n);
+    }
+    if (s.sparse_slots > 0 && s.sparse_slots_narrow > 0 &&
+        (ninst + s.sparse_slots_narrow - 1) / s.sparse_slots_narrow < (ninst + s.sparse_slots - 1) / s.sparse_slots) {
+      a.piece_blocks = pb_n;
+      sparse_decode_kernel<T, D, G, kNarrowWaves, true><<<dim3(1, ninst), kNarrowWaves * kWave, lds_n, st>>>(a);
+      return hipGetLastError();
+    }
+  }
+  sparse_decode_kernel<T, D, G, kAttnWaves, false><<<dim3(a.n_split, ninst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.n_split == 1) return e;
   const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G) + sizeof(int) * a.k;
@@ -189,6 +219,7 @@ hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void
   a.n_split = s.n_split;
   a.blk_per_split = (s.k + s.n_split - 1) / s.n_split;
   a.inst0 = inst0;
+  a.piece_blocks = s.k;
   a.table = s.table; a.n_phys = s.n_phys;
   AP_DISPATCH(run_sparse, s, ninst, a, st)
 }

@@ -102,9 +102,11 @@ template <typename T, int D, int G> struct Geom {
 //               it fits into the region that holds the output partials later (sparse decode)
 // fp32 K/V keeps the VALU form: LPT adjacent lanes share one row, 16 bytes each.
 constexpr int kStageRowPad = 16;   // bytes added to a staged K row so that 16 rows spread over the LDS banks
-template <int D, int ROWS = kGroupTokens> constexpr int k_stage_floats() { return kAttnWaves * ROWS * (D * 2 + kStageRowPad) / 4; }
+template <int D, int ROWS = kGroupTokens, int NW = kAttnWaves> constexpr int k_stage_floats() {
+  return NW * ROWS * (D * 2 + kStageRowPad) / 4;
+}
 
-template <typename T, int D, int G, int STAGE, class BlockOf, class PhysOf>
+template <typename T, int D, int G, int STAGE, int NW = kAttnWaves, class BlockOf, class PhysOf>
 __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T* __restrict__ K_inst, int b, int log2b,
                                           int t_cur, int ntok, BlockOf block_of, PhysOf phys_of, float* s_p, int ld,
                                           float* s_stage) {
@@ -172,11 +174,11 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
       uint4 v[NPRE][NLK];
 #pragma unroll
       for (int i = 0; i < NPRE; ++i)
-        if (wave + i * kAttnWaves < npass) load_pass(wave + i * kAttnWaves, v[i]);
-      for (int ps = wave; ps < npass; ps += NPRE * kAttnWaves) {
+        if (wave + i * NW < npass) load_pass(wave + i * NW, v[i]);
+      for (int ps = wave; ps < npass; ps += NPRE * NW) {
 #pragma unroll
         for (int i = 0; i < NPRE; ++i)
-          if (ps + i * kAttnWaves < npass) do_pass(ps + i * kAttnWaves, v[i], ps + (i + NPRE) * kAttnWaves);
+          if (ps + i * NW < npass) do_pass(ps + i * NW, v[i], ps + (i + NPRE) * NW);
       }
     }
   } else {
@@ -194,7 +196,7 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
 #pragma unroll
       for (int e = 0; e < E; ++e) qr[h][e] = f[e] * scale;
     }
-    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+    for (int grp = wave; grp < ngroups; grp += NW) {
       uint4 kw[NL];
       int gtok[NL];
 #pragma unroll
@@ -228,18 +230,21 @@ __device__ __forceinline__ void qk_logits(const T* __restrict__ q_inst, const T*
   }
 }
 
-// Phase 2.  Leaves p in s_p, (M, L) in s_m / s_l, per (head, block) max p in s_bmp[h * nblk + jb].
+// Phase 2.  Leaves p in s_p, (M, L) in s_m / s_l, per (head, block) max p in s_bmp[h * bmp_ld + jb].
 // One wave per head; a lane handles four consecutive tokens per 16-byte LDS access (ntok and ld are multiples
 // of the block size, hence of 4), so the b / 4 adjacent lanes of a block find its maximum with DPP moves.
-template <int G>
-__device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int b, int nblk, float* s_m, float* s_l,
-                                     float* s_bmp) {
+// With s_alpha the statistics run on over several calls (pieces of one list): M is the maximum so far, p is
+// relative to it, L is carried over as L * alpha + sum with alpha = exp(M_before - M), which s_alpha[h]
+// receives for the caller to rescale what it has accumulated (0 on the first piece, M_before = -inf).
+template <int G, int NW = kAttnWaves>
+__device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int b, int bmp_ld, float* s_m, float* s_l,
+                                     float* s_bmp, float* s_alpha = nullptr) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int nquad = ntok >> 2;
   const int lanes_per_blk = b >> 2;                      // 2, 4, 8 or 16
   const int blk_shift = __ffs(lanes_per_blk) - 1;
-  for (int h = wave; h < G; h += kAttnWaves) {
+  for (int h = wave; h < G; h += NW) {
     float4* prow = reinterpret_cast<float4*>(s_p + (size_t)h * ld);
     float m = -INFINITY;
     for (int qd = lane; qd < nquad; qd += kWave) {
@@ -247,6 +252,12 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
       m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
     }
     m = wave_max(m);
+    float m_old = -INFINITY, l_old = 0.f;
+    if (s_alpha != nullptr) {
+      m_old = s_m[h];
+      l_old = s_l[h];
+      m = fmaxf(m, m_old);
+    }
     float sum = 0.f;
     for (int q0 = 0; q0 < nquad; q0 += kWave) {          // uniform trip count: the DPP moves need every lane
       const int qd = q0 + lane;
@@ -262,10 +273,15 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
       if (lanes_per_blk >= 4) bm = fmaxf(bm, dpp_move<0x4E>(bm));           // quad_perm [2,3,0,1]
       if (lanes_per_blk >= 8) bm = fmaxf(bm, dpp_move<0x141>(bm));          // row_half_mirror
       if (lanes_per_blk >= 16) bm = fmaxf(bm, dpp_move<0x140>(bm));         // row_mirror
-      if (qd < nquad && (lane & (lanes_per_blk - 1)) == 0) s_bmp[h * nblk + (qd >> blk_shift)] = bm;
+      if (qd < nquad && (lane & (lanes_per_blk - 1)) == 0) s_bmp[h * bmp_ld + (qd >> blk_shift)] = bm;
     }
     sum = wave_sum(sum);
-    if (lane == 0) { s_m[h] = m; s_l[h] = sum; }
+    if (lane == 0) {
+      const float alpha = (m_old == -INFINITY) ? 0.f : __expf(m_old - m);
+      s_m[h] = m;
+      s_l[h] = l_old * alpha + sum;
+      if (s_alpha != nullptr) s_alpha[h] = alpha;
+    }
   }
   __syncthreads();
 }
@@ -286,8 +302,8 @@ __device__ __forceinline__ void write_row(float* __restrict__ row, int nb_cap, c
 
 constexpr int kSparseStage = 8;
 // Floats of the region shared by the staged K tile (phase 1) and the per-wave output partials (after phase 3).
-template <int D, int G> constexpr int sparse_acc_floats() {
-  return kAttnWaves * G * D > k_stage_floats<D, kSparseStage>() ? kAttnWaves * G * D : k_stage_floats<D, kSparseStage>();
+template <int D, int G, int NW> constexpr int sparse_acc_floats() {
+  return NW * G * D > k_stage_floats<D, kSparseStage, NW>() ? NW * G * D : k_stage_floats<D, kSparseStage, NW>();
 }
 
 struct SparseArgs {
@@ -298,14 +314,19 @@ struct SparseArgs {
   int t_cap, nb_cap, k, b, log2b, t_cur, nb_cur, n_split, blk_per_split, inst0;
   const int32_t* table;           // block table [n_inst][nb_cap] of a paged cache, or null
   int n_phys;                     // blocks in the pool (table entries are clamped into it)
+  int piece_blocks;               // list positions whose probabilities are in LDS at a time
 };
 
-// Sparse decode of instance `inst`, split `split`, by one workgroup of kAttnThreads threads.
+// Sparse decode of instance `inst`, split `split`, by one workgroup of NW waves.
+// The list is worked off in pieces of a.piece_blocks positions - logits, softmax statistics, acc += p * V per
+// piece, the statistics running on and acc rescaled when the maximum moves - so that the LDS holds the
+// probabilities of one piece only.  PIECED = false: a.piece_blocks covers the list, one piece, no rescaling
+// (and the accumulators are not live during phase 1).
 // smem: sparse_lds_floats(...) floats of LDS, 16-byte aligned.
-template <typename T, int D, int G>
+template <typename T, int D, int G, int NW, bool PIECED>
 __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst, int split, float* smem) {
   using Ge = Geom<T, D, G>;
-  constexpr int E = Ge::E, LPT = Ge::LPT, TPI = Ge::TPI, NL = Ge::NL;
+  constexpr int E = Ge::E, LPT = Ge::LPT, NL = Ge::NL, NT = NW * kWave;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int dpart = lane % LPT, tslot = lane / LPT;
 
@@ -315,15 +336,18 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
   const int j1 = (a.n_split == 1) ? cnt : min(cnt, j0 + a.blk_per_split);
   const int nblk = j1 - j0;
   const int nblk_cap = (a.n_split == 1) ? a.k : a.blk_per_split;
-  const int ld = nblk_cap * a.b;
-  const int ntok = nblk * a.b;
+  const int pb = PIECED ? min(a.piece_blocks, nblk_cap) : nblk_cap;   // positions per piece
+  const int n_pieces_cap = (nblk_cap + pb - 1) / pb;
+  const int ld = pb * a.b;
 
   float* s_p = smem;                                   // [G][ld]
   float* s_acc = s_p + G * ld;                         // [waves][G][D]
-  float* s_bmp = s_acc + sparse_acc_floats<D, G>();    // [G][nblk_cap]
-  float* s_m = s_bmp + G * nblk_cap;                   // [G]
-  float* s_l = s_m + G;                                // [G]
-  int* s_idx = reinterpret_cast<int*>(s_l + G);        // [nblk_cap] logical block of each list position
+  float* s_bmp = s_acc + sparse_acc_floats<D, G, NW>();   // [G][nblk_cap]
+  float* s_m = s_bmp + G * nblk_cap;                   // [G] running maximum
+  float* s_l = s_m + G;                                // [G] running sum
+  float* s_alpha = s_l + G;                            // [G] rescaling factor of the piece at hand
+  float* s_mpiece = s_alpha + G;                       // [n_pieces_cap][G] maximum the piece's p are relative to
+  int* s_idx = reinterpret_cast<int*>(s_mpiece + n_pieces_cap * G);   // [nblk_cap] logical block of each position
   int* s_phys = s_idx + nblk_cap;                      // [nblk_cap] its place in K / V
   // For the pooled row, written whole by the workgroup that has the whole list: one bit per block (is it
   // listed) and, per 32-block word, the number of listed blocks before it, so that a column finds its list
@@ -334,17 +358,18 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
   const bool whole_row = a.n_split == 1;
 
   if (whole_row) {
-    for (int w = threadIdx.x; w < nwords; w += kAttnThreads) s_listed[w] = 0u;
-    __syncthreads();
+    for (int w = threadIdx.x; w < nwords; w += NT) s_listed[w] = 0u;
   }
-  for (int j = threadIdx.x; j < nblk; j += kAttnThreads) {
+  if (threadIdx.x < G) { s_m[threadIdx.x] = -INFINITY; s_l[threadIdx.x] = 0.f; }
+  __syncthreads();
+  for (int j = threadIdx.x; j < nblk; j += NT) {
     const int blk = min(max(a.idx[(size_t)inst * a.k + j0 + j], 0), a.nb_cur - 1);
     s_idx[j] = blk;
     s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + blk], 0), a.n_phys - 1) : blk;
     if (whole_row) atomicOr(&s_listed[blk >> 5], 1u << (blk & 31));
   }
   __syncthreads();
-  if (whole_row && wave == kAttnWaves - 1) {           // exclusive prefix sum of the words' bit counts
+  if (whole_row && wave == NW - 1) {                   // exclusive prefix sum of the words' bit counts
     const int per_lane = (nwords + kWave - 1) / kWave;
     const int w0 = lane * per_lane;
     int mine = 0;
@@ -373,26 +398,39 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[h][e] = 0.f;
 
-  if (nblk > 0) {
-    // (the staged K tile lives where the waves' output partials go after phase 3)
-    qk_logits<T, D, G, kSparseStage>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return s_idx[jb]; },
-                       [&](int jb) { return s_phys[jb]; }, s_p, ld, s_acc);
+  int p0 = 0, piece = 0;
+  if (nblk > 0) do {
+    const int nb_p = min(pb, nblk - p0);
+    const int ntok = nb_p * a.b;
+    // (the staged K tile lives where the waves' output partials go after the last piece)
+    qk_logits<T, D, G, kSparseStage, NW>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok,
+                                         [&](int jb) { return s_idx[p0 + jb]; },
+                                         [&](int jb) { return s_phys[p0 + jb]; }, s_p, ld, s_acc);
     __syncthreads();
-    softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
+    softmax_stats<G, NW>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp + p0, s_alpha);
+    if (threadIdx.x < G) s_mpiece[piece * G + threadIdx.x] = s_m[threadIdx.x];
+    if (PIECED && piece > 0) {                         // the maximum may have moved: bring acc along
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float al = s_alpha[h];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[h][e] *= al;
+      }
+    }
 
     // Phase 3: acc += p * V.  A lane group takes NL consecutive tokens of a 16-token group (they lie in one
     // block, so one table lookup places them), load instruction i covers the i-th row of each of the TPI lane
-    // groups - whole 256-byte rows as before - and the NL probabilities of a head come in one LDS access.
+    // groups - whole 256-byte rows - and the NL probabilities of a head come in one LDS access.
     const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
     static_assert(NL == 2 || NL == 4 || NL == 8, "probabilities are fetched as 8- or 16-byte vectors");
-    for (int grp = wave; grp < ngroups; grp += kAttnWaves) {
+    for (int grp = wave; grp < ngroups; grp += NW) {
       const int tau0 = grp * kGroupTokens + tslot * NL;   // ntok is a multiple of 8 >= NL: all NL tokens or none
       const bool live = tau0 < ntok;
       uint4 vw[NL];
 #pragma unroll
       for (int i = 0; i < NL; ++i) vw[i] = make_uint4(0, 0, 0, 0);
       if (live) {
-        const int ptok0 = s_phys[tau0 >> a.log2b] * a.b + (tau0 & (a.b - 1));
+        const int ptok0 = s_phys[p0 + (tau0 >> a.log2b)] * a.b + (tau0 & (a.b - 1));
 #pragma unroll
         for (int i = 0; i < NL; ++i) vw[i] = ld_stream(V_inst + (size_t)(ptok0 + i) * D + dpart * E);
       }
@@ -423,8 +461,17 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
         }
       }
     }
-  } else {
-    if (threadIdx.x < G) { s_m[threadIdx.x] = -INFINITY; s_l[threadIdx.x] = 0.f; }
+    __syncthreads();                                   // the next piece, or the partials, overwrite what was read
+    p0 += pb;
+    ++piece;
+  } while (PIECED && p0 < nblk);
+
+  // Block maxima of earlier pieces are relative to the maximum of their time: bring them to the final one.
+  if (PIECED && nblk > pb) {
+    for (int pair = threadIdx.x; pair < G * nblk; pair += NT) {
+      const int h = pair / nblk, jb = pair - h * nblk;
+      s_bmp[pair] *= __expf(s_mpiece[(jb / pb) * G + h] - s_m[h]);
+    }
   }
 
   // Sum the token slots of a wave (lanes that hold the same dims), then the waves through LDS.
@@ -446,16 +493,16 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
   __syncthreads();
 
   if (a.n_split == 1) {
-    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+    for (int o = threadIdx.x; o < G * D; o += NT) {
       float v = 0.f;
 #pragma unroll
-      for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
+      for (int w = 0; w < NW; ++w) v += s_acc[w * G * D + o];
       const float L = s_l[o / D];
       a.out[(size_t)inst * G * D + o] = L > 0.f ? v / L : 0.f;      // an empty list gives a zero output
     }
     // Pooled row: column j of a listed block gets the largest block maximum over the heads, the rest zero.
     float* row = a.row + (size_t)inst * a.row_stride;
-    for (int j = threadIdx.x; j < a.nb_cap; j += kAttnThreads) {
+    for (int j = threadIdx.x; j < a.nb_cap; j += NT) {
       const uint32_t word = s_listed[j >> 5];
       float mx = 0.f;
       if ((word >> (j & 31)) & 1u) {
@@ -467,17 +514,17 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     }
   } else {
     const size_t ps = (size_t)inst * a.n_split + split;
-    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+    for (int o = threadIdx.x; o < G * D; o += NT) {
       float v = 0.f;
 #pragma unroll
-      for (int w = 0; w < kAttnWaves; ++w) v += s_acc[w * G * D + o];
+      for (int w = 0; w < NW; ++w) v += s_acc[w * G * D + o];
       a.part_acc[ps * G * D + o] = v;
     }
     if (threadIdx.x < G) {
       a.part_ml[(ps * G + threadIdx.x) * 2 + 0] = s_m[threadIdx.x];
       a.part_ml[(ps * G + threadIdx.x) * 2 + 1] = s_l[threadIdx.x];
     }
-    for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+    for (int pair = threadIdx.x; pair < G * nblk; pair += NT) {
       const int h = pair / nblk, jb = pair - h * nblk;
       a.part_bmp[((size_t)inst * G + h) * a.k + j0 + jb] = s_bmp[pair];
     }
@@ -485,10 +532,13 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 }
 
 
-// LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens out of nb_cap.
-template <int D, int G> inline size_t sparse_lds_floats(int nblk_cap, int b, int nb_cap) {
-  return (size_t)G * nblk_cap * b + sparse_acc_floats<D, G>() + (size_t)G * nblk_cap + 2 * G + 2 * nblk_cap +
-         2 * (size_t)((nb_cap + 31) / 32);
+// LDS floats sparse_decode_body needs for a list of up to nblk_cap blocks of b tokens out of nb_cap, worked off
+// in pieces of piece_blocks.
+template <int D, int G, int NW> inline size_t sparse_lds_floats(int nblk_cap, int piece_blocks, int b, int nb_cap) {
+  const int pb = piece_blocks < nblk_cap ? piece_blocks : nblk_cap;
+  const int n_pieces = (nblk_cap + pb - 1) / pb;
+  return (size_t)G * pb * b + sparse_acc_floats<D, G, NW>() + (size_t)G * nblk_cap + 3 * G + (size_t)n_pieces * G +
+         2 * nblk_cap + 2 * (size_t)((nb_cap + 31) / 32);
 }
 
 }  // namespace
