@@ -4,8 +4,10 @@
 namespace ap {
 namespace {
 
+// (the two-wave form is only worth launching if eight of its workgroups fit a CU: four waves per SIMD, 128 VGPRs)
 template <typename T, int D, int G, int NW, bool PIECED>
-__global__ __launch_bounds__(NW * kWave) void sparse_decode_kernel(SparseArgs a) {
+__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == kNarrowWaves ? 4 : 1)))
+void sparse_decode_kernel(SparseArgs a) {
   extern __shared__ __align__(16) float smem[];
   sparse_decode_body<T, D, G, NW, PIECED>(a, a.inst0 + blockIdx.y, blockIdx.x, smem);
 }
@@ -153,7 +155,7 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   // empty, and every round pays its start-up and drain.  Two-wave workgroups that keep the probabilities of
   // kNarrowPieceTokens tokens at a time are small enough for more of them to be resident; they are used when
   // that saves a round.
-  if (a.n_split == 1 && nblk_cap * a.b > kNarrowPieceTokens) {
+  if constexpr (G <= 4) if (a.n_split == 1 && nblk_cap * a.b > kNarrowPieceTokens) {   // (g = 8 would spill in that form)
     const int pb_n = kNarrowPieceTokens / a.b;
     const size_t lds_n = sizeof(float) * sparse_lds_floats<D, G, kNarrowWaves>(nblk_cap, pb_n, a.b, a.nb_cap);
     if (s.sparse_slots < 0) {

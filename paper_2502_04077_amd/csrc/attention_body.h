@@ -244,30 +244,52 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
   const int nquad = ntok >> 2;
   const int lanes_per_blk = b >> 2;                      // 2, 4, 8 or 16
   const int blk_shift = __ffs(lanes_per_blk) - 1;
-  for (int h = wave; h < G; h += NW) {
-    float4* prow = reinterpret_cast<float4*>(s_p + (size_t)h * ld);
-    float m = -INFINITY;
-    for (int qd = lane; qd < nquad; qd += kWave) {
-      const float4 v = prow[qd];
-      m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+  // Heads wave, wave + NW, ... of this wave are worked on together: their loads, reductions and exponentials
+  // are independent chains that hide each other's latency.
+  constexpr int HPW = (G + NW - 1) / NW;
+  float m[HPW], m_old[HPW], l_old[HPW], sum[HPW];
+#pragma unroll
+  for (int j = 0; j < HPW; ++j) { m[j] = -INFINITY; m_old[j] = -INFINITY; l_old[j] = 0.f; sum[j] = 0.f; }
+  for (int qd = lane; qd < nquad; qd += kWave) {
+#pragma unroll
+    for (int j = 0; j < HPW; ++j) {
+      const int h = wave + j * NW;
+      if (h < G) {
+        const float4 v = reinterpret_cast<const float4*>(s_p + (size_t)h * ld)[qd];
+        m[j] = fmaxf(m[j], fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+      }
     }
-    m = wave_max(m);
-    float m_old = -INFINITY, l_old = 0.f;
-    if (s_alpha != nullptr) {
-      m_old = s_m[h];
-      l_old = s_l[h];
-      m = fmaxf(m, m_old);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+    for (int j = 0; j < HPW; ++j) m[j] = fmaxf(m[j], __shfl_xor(m[j], o, 64));
+  }
+  if (s_alpha != nullptr) {
+#pragma unroll
+    for (int j = 0; j < HPW; ++j) {
+      const int h = wave + j * NW;
+      if (h < G) {
+        m_old[j] = s_m[h];
+        l_old[j] = s_l[h];
+        m[j] = fmaxf(m[j], m_old[j]);
+      }
     }
-    float sum = 0.f;
-    for (int q0 = 0; q0 < nquad; q0 += kWave) {          // uniform trip count: the DPP moves need every lane
-      const int qd = q0 + lane;
+  }
+  for (int q0 = 0; q0 < nquad; q0 += kWave) {            // uniform trip count: the DPP moves need every lane
+    const int qd = q0 + lane;
+#pragma unroll
+    for (int j = 0; j < HPW; ++j) {
+      const int h = wave + j * NW;
+      if (h >= G) continue;                              // (wave-uniform)
+      float4* prow = reinterpret_cast<float4*>(s_p + (size_t)h * ld);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (qd < nquad) {
         v = prow[qd];
-        v.x = __expf(v.x - m); v.y = __expf(v.y - m); v.z = __expf(v.z - m); v.w = __expf(v.w - m);
+        v.x = __expf(v.x - m[j]); v.y = __expf(v.y - m[j]); v.z = __expf(v.z - m[j]); v.w = __expf(v.w - m[j]);
         prow[qd] = v;
       }
-      sum += (v.x + v.y) + (v.z + v.w);
+      sum[j] += (v.x + v.y) + (v.z + v.w);
       float bm = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
       bm = fmaxf(bm, dpp_move<0xB1>(bm));                                   // quad_perm [1,0,3,2]
       if (lanes_per_blk >= 4) bm = fmaxf(bm, dpp_move<0x4E>(bm));           // quad_perm [2,3,0,1]
@@ -275,12 +297,22 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
       if (lanes_per_blk >= 16) bm = fmaxf(bm, dpp_move<0x140>(bm));         // row_mirror
       if (qd < nquad && (lane & (lanes_per_blk - 1)) == 0) s_bmp[h * bmp_ld + (qd >> blk_shift)] = bm;
     }
-    sum = wave_sum(sum);
-    if (lane == 0) {
-      const float alpha = (m_old == -INFINITY) ? 0.f : __expf(m_old - m);
-      s_m[h] = m;
-      s_l[h] = l_old * alpha + sum;
-      if (s_alpha != nullptr) s_alpha[h] = alpha;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+#pragma unroll
+    for (int j = 0; j < HPW; ++j) sum[j] += __shfl_xor(sum[j], o, 64);
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int j = 0; j < HPW; ++j) {
+      const int h = wave + j * NW;
+      if (h < G) {
+        const float alpha = (m_old[j] == -INFINITY) ? 0.f : __expf(m_old[j] - m[j]);
+        s_m[h] = m[j];
+        s_l[h] = l_old[j] * alpha + sum[j];
+        if (s_alpha != nullptr) s_alpha[h] = alpha;
+      }
     }
   }
   __syncthreads();
