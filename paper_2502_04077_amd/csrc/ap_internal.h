@@ -12,8 +12,7 @@ namespace ap {
 constexpr int kWave = 64;
 constexpr int kAttnThreads = 256;             // 4 waves per attention workgroup
 constexpr int kAttnWaves = kAttnThreads / kWave;
-constexpr int kNarrowWaves = 2;               // waves of the sparse-decode workgroup used when instances outnumber the wide ones' slots
-constexpr int kNarrowPieceTokens = 512;       // tokens whose probabilities such a workgroup holds in LDS at a time
+constexpr int kNarrowPieceTokens = 512;       // tokens whose probabilities a two- or one-wave sparse-decode workgroup holds in LDS at a time
 constexpr int kGroupTokens = 16;              // tokens one wave covers per load group (4 x dwordx4 loads)
 constexpr int kCalibChunkTokens = 1024;       // tokens per calibration workgroup
 
@@ -29,8 +28,8 @@ struct Shape {
   int n_inst, g, d, b, H, R, t_cap, nb_cap, k, n_sink, n_local, c1, c2, kv_dtype;
   int predictor_mfma; // incremental predictor on f16 MFMA (8/8 and 16/32 channels)
   int n_split;        // workgroups per instance in sparse decode
-  // sparse-decode workgroups the device holds at once, four-wave and two-wave form (found at the first launch)
-  mutable int sparse_slots = -1, sparse_slots_narrow = -1;
+  // sparse-decode workgroups the device holds at once in the four-, two- and one-wave form (found at the first launch)
+  mutable int sparse_slots[3] = {-1, -1, -1};
   int calib_chunks;   // max workgroups per instance in calibrate
   const int32_t* table;  // device block table of a paged K/V cache [n_inst][nb_cap], or null (caller-owned)
   int n_phys;            // physical blocks in the pool

@@ -4,9 +4,9 @@
 namespace ap {
 namespace {
 
-// (the two-wave form is only worth launching if eight of its workgroups fit a CU: four waves per SIMD, 128 VGPRs)
+// (the narrow forms are only worth launching if many of their workgroups fit a CU: four waves per SIMD, 128 VGPRs)
 template <typename T, int D, int G, int NW, bool PIECED>
-__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW == kNarrowWaves ? 4 : 1)))
+__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW < kAttnWaves ? 4 : 1)))
 void sparse_decode_kernel(SparseArgs a) {
   extern __shared__ __align__(16) float smem[];
   sparse_decode_body<T, D, G, NW, PIECED>(a, a.inst0 + blockIdx.y, blockIdx.x, smem);
@@ -152,21 +152,28 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   a.piece_blocks = nblk_cap;
   const size_t lds = sizeof(float) * sparse_lds_floats<D, G, kAttnWaves>(nblk_cap, nblk_cap, a.b, a.nb_cap);
   // More instances than the chip holds four-wave workgroups: the launch runs in rounds, the last one part
-  // empty, and every round pays its start-up and drain.  Two-wave workgroups that keep the probabilities of
-  // kNarrowPieceTokens tokens at a time are small enough for more of them to be resident; they are used when
-  // that saves a round.
-  if constexpr (G <= 4) if (a.n_split == 1 && nblk_cap * a.b > kNarrowPieceTokens) {   // (g = 8 would spill in that form)
+  // empty, and every round pays its start-up and drain.  Workgroups of two waves or one that keep the
+  // probabilities of kNarrowPieceTokens tokens at a time are small enough for more of them to be resident; the
+  // widest form with the fewest rounds is used.
+  if constexpr (G <= 4) if (a.n_split == 1 && nblk_cap * a.b > kNarrowPieceTokens) {   // (g = 8 would spill in those forms)
     const int pb_n = kNarrowPieceTokens / a.b;
-    const size_t lds_n = sizeof(float) * sparse_lds_floats<D, G, kNarrowWaves>(nblk_cap, pb_n, a.b, a.nb_cap);
-    if (s.sparse_slots < 0) {
-      s.sparse_slots = resident_workgroups(sparse_decode_kernel<T, D, G, kAttnWaves, false>, kAttnThreads, lds);
-      s.sparse_slots_narrow = resident_workgroups(sparse_decode_kernel<T, D, G, kNarrowWaves, true>,
-                                                  kNarrowWaves * kWave, lds_n);
+    const size_t lds_2 = sizeof(float) * sparse_lds_floats<D, G, 2>(nblk_cap, pb_n, a.b, a.nb_cap);
+    const size_t lds_1 = sizeof(float) * sparse_lds_floats<D, G, 1>(nblk_cap, pb_n, a.b, a.nb_cap);
+    if (s.sparse_slots[0] < 0) {
+      s.sparse_slots[0] = resident_workgroups(sparse_decode_kernel<T, D, G, kAttnWaves, false>, kAttnThreads, lds);
+      s.sparse_slots[1] = resident_workgroups(sparse_decode_kernel<T, D, G, 2, true>, 2 * kWave, lds_2);
+      s.sparse_slots[2] = resident_workgroups(sparse_decode_kernel<T, D, G, 1, true>, kWave, lds_1);
     }
-    if (s.sparse_slots > 0 && s.sparse_slots_narrow > 0 &&
-        (ninst + s.sparse_slots_narrow - 1) / s.sparse_slots_narrow < (ninst + s.sparse_slots - 1) / s.sparse_slots) {
+    int form = 0, best_rounds = 0;
+    for (int f = 0; f < 3; ++f) {
+      if (s.sparse_slots[f] <= 0) { form = 0; break; }     // occupancy unknown: stay with the four-wave form
+      const int rounds = (ninst + s.sparse_slots[f] - 1) / s.sparse_slots[f];
+      if (f == 0 || rounds < best_rounds) { form = f; best_rounds = rounds; }
+    }
+    if (form != 0) {
       a.piece_blocks = pb_n;
-      sparse_decode_kernel<T, D, G, kNarrowWaves, true><<<dim3(1, ninst), kNarrowWaves * kWave, lds_n, st>>>(a);
+      if (form == 1) sparse_decode_kernel<T, D, G, 2, true><<<dim3(1, ninst), 2 * kWave, lds_2, st>>>(a);
+      else sparse_decode_kernel<T, D, G, 1, true><<<dim3(1, ninst), kWave, lds_1, st>>>(a);
       return hipGetLastError();
     }
   }
