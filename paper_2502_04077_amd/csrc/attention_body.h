@@ -438,6 +438,24 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     qk_logits<T, D, G, kSparseStage, NW>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok,
                                          [&](int jb) { return s_idx[p0 + jb]; },
                                          [&](int jb) { return s_phys[p0 + jb]; }, s_p, ld, s_acc);
+    // The V rows of this wave's first 16-token group do not depend on the probabilities: with PIECED (all
+    // workgroups of the launch resident and in step, so nobody else fills the gap) they are requested before
+    // the softmax pass and arrive while it runs - where the registers allow it (with g = 4 the kernel is at its
+    // 128 VGPRs already and would spill: 0.201 vs 0.183 ms at cfg2; with g = 1 it gains 1.5 % at cfg4).
+    constexpr bool kEarlyV = PIECED && G <= 2;
+    const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
+    uint4 vw[NL];
+    auto load_v = [&](int grp) __attribute__((always_inline)) {
+      const int tau0 = grp * kGroupTokens + tslot * NL;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) vw[i] = make_uint4(0, 0, 0, 0);
+      if (tau0 < ntok) {
+        const int ptok0 = s_phys[p0 + (tau0 >> a.log2b)] * a.b + (tau0 & (a.b - 1));
+#pragma unroll
+        for (int i = 0; i < NL; ++i) vw[i] = ld_stream(V_inst + (size_t)(ptok0 + i) * D + dpart * E);
+      }
+    };
+    if (kEarlyV && wave < ngroups) load_v(wave);
     __syncthreads();
     softmax_stats<G, NW>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp + p0, s_alpha);
     if (threadIdx.x < G) s_mpiece[piece * G + threadIdx.x] = s_m[threadIdx.x];
@@ -453,19 +471,11 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     // Phase 3: acc += p * V.  A lane group takes NL consecutive tokens of a 16-token group (they lie in one
     // block, so one table lookup places them), load instruction i covers the i-th row of each of the TPI lane
     // groups - whole 256-byte rows - and the NL probabilities of a head come in one LDS access.
-    const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
     static_assert(NL == 2 || NL == 4 || NL == 8, "probabilities are fetched as 8- or 16-byte vectors");
     for (int grp = wave; grp < ngroups; grp += NW) {
       const int tau0 = grp * kGroupTokens + tslot * NL;   // ntok is a multiple of 8 >= NL: all NL tokens or none
       const bool live = tau0 < ntok;
-      uint4 vw[NL];
-#pragma unroll
-      for (int i = 0; i < NL; ++i) vw[i] = make_uint4(0, 0, 0, 0);
-      if (live) {
-        const int ptok0 = s_phys[p0 + (tau0 >> a.log2b)] * a.b + (tau0 & (a.b - 1));
-#pragma unroll
-        for (int i = 0; i < NL; ++i) vw[i] = ld_stream(V_inst + (size_t)(ptok0 + i) * D + dpart * E);
-      }
+      if (!kEarlyV || grp != wave) load_v(grp);
       float pw[G][NL];
 #pragma unroll
       for (int h = 0; h < G; ++h) {
