@@ -30,6 +30,7 @@ struct Shape {
   int n_split;        // workgroups per instance in sparse decode
   // sparse-decode workgroups the device holds at once in the four-, two- and one-wave form (found at the first launch)
   mutable int sparse_slots[3] = {-1, -1, -1};
+  mutable int calib_slots = -1;   // calibration workgroups the device holds at once
   int calib_chunks;   // max workgroups per instance in calibrate
   const int32_t* table;  // device block table of a paged K/V cache [n_inst][nb_cap], or null (caller-owned)
   int n_phys;            // physical blocks in the pool
@@ -43,6 +44,7 @@ struct WsLayout {
   size_t cal_ml;      // [n_inst][calib_chunks][g][2]
   size_t cal_bmp;     // [n_inst][g][nb_cap]
   size_t pred_state;  // [n_inst][nb_cap]               interior state of a full-tile prediction without a caller state
+  size_t counters;    // [4] ints                       work counters of persistent kernels (zeroed by the launch that uses them)
   size_t total;       // floats
 };
 

@@ -27,6 +27,7 @@ WsLayout ws_layout(const Shape& s) {
   w.cal_ml = o;   o = align4(o + (size_t)s.n_inst * s.calib_chunks * s.g * 2);
   w.cal_bmp = o;  o = align4(o + (size_t)s.n_inst * s.g * s.nb_cap);
   w.pred_state = o; o = align4(o + (size_t)s.n_inst * s.nb_cap);
+  w.counters = o; o = align4(o + 4);
   w.total = o;
   return w;
 }

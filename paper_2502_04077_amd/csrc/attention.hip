@@ -60,44 +60,60 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs
 struct CalibArgs {
   const void* q; const void* K;
   float* row; float* cal_ml; float* cal_bmp;
+  int* counter;                   // next (instance, chunk) unit to hand out; zero at launch
+  int n_units;                    // n_inst * n_chunks
   int t_cap, nb_cap, b, log2b, t_cur, nb_cur, chunk_blocks, n_chunks, chunk_slots;
   const int32_t* table;
   int n_phys;
 };
 
+__global__ void zero_counter_kernel(int* counter) { *counter = 0; }
+
+// Workgroups are dealt to the XCDs in turn, and the XCDs do not stream equally fast (in the sparse-decode kernel the
+// slowest ends 12 % after the mean): a launch of one workgroup per chunk ends with its slowest XCD.  So the
+// grid is what the chip holds at once, and every workgroup takes (instance, chunk) units off a counter until
+// none is left; a unit is 1024 tokens, 30-40 us of streaming.
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void calibrate_kernel(CalibArgs a) {
   extern __shared__ __align__(16) float smem[];
-  const int inst = blockIdx.y, chunk = blockIdx.x;
-  const int c0 = chunk * a.chunk_blocks;
-  const int nblk = min(a.chunk_blocks, a.nb_cur - c0);
-  const int ld = a.chunk_blocks * a.b;
-  const int ntok = nblk * a.b;
-  float* s_p = smem;                    // [G][ld]
-  float* s_bmp = s_p + G * ld;          // [G][chunk_blocks]
-  float* s_m = s_bmp + G * a.chunk_blocks;
-  float* s_l = s_m + G;
-  int* s_phys = reinterpret_cast<int*>(s_l + G);   // [chunk_blocks] place of each block of the chunk in K
-  float* s_stage = smem + (((reinterpret_cast<float*>(s_phys + a.chunk_blocks) - smem) + 3) & ~3);
+  __shared__ int s_unit;
+  for (;;) {
+    if (threadIdx.x == 0) s_unit = atomicAdd(a.counter, 1);
+    __syncthreads();
+    const int unit = s_unit;
+    if (unit >= a.n_units) break;                        // (the same for every thread; every workgroup gets here)
+    const int inst = unit / a.n_chunks, chunk = unit - inst * a.n_chunks;
+    const int c0 = chunk * a.chunk_blocks;
+    const int nblk = min(a.chunk_blocks, a.nb_cur - c0);
+    const int ld = a.chunk_blocks * a.b;
+    const int ntok = nblk * a.b;
+    float* s_p = smem;                    // [G][ld]
+    float* s_bmp = s_p + G * ld;          // [G][chunk_blocks]
+    float* s_m = s_bmp + G * a.chunk_blocks;
+    float* s_l = s_m + G;
+    int* s_phys = reinterpret_cast<int*>(s_l + G);   // [chunk_blocks] place of each block of the chunk in K
+    float* s_stage = smem + (((reinterpret_cast<float*>(s_phys + a.chunk_blocks) - smem) + 3) & ~3);
 
-  for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
-    s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + c0 + j], 0), a.n_phys - 1) : c0 + j;
-  __syncthreads();
-  const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
-  const T* K_inst = static_cast<const T*>(a.K) + (a.table ? 0 : (size_t)inst * a.t_cap * D);
-  constexpr int kStage = std::is_same<T, bf16_t>::value ? kGroupTokens : 0;
-  qk_logits<T, D, G, kStage>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; },
-                     [&](int jb) { return s_phys[jb]; }, s_p, ld, s_stage);
-  __syncthreads();
-  softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
-  for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
-    const int h = pair / nblk, jb = pair - h * nblk;
-    a.cal_bmp[((size_t)inst * G + h) * a.nb_cap + c0 + jb] = s_bmp[pair];
-  }
-  if (threadIdx.x < G) {
-    float* ml = a.cal_ml + (((size_t)inst * a.chunk_slots + chunk) * G + threadIdx.x) * 2;
-    ml[0] = s_m[threadIdx.x];
-    ml[1] = s_l[threadIdx.x];
+    for (int j = threadIdx.x; j < nblk; j += kAttnThreads)
+      s_phys[j] = a.table ? min(max(a.table[(size_t)inst * a.nb_cap + c0 + j], 0), a.n_phys - 1) : c0 + j;
+    __syncthreads();
+    const T* q_inst = static_cast<const T*>(a.q) + (size_t)inst * G * D;
+    const T* K_inst = static_cast<const T*>(a.K) + (a.table ? 0 : (size_t)inst * a.t_cap * D);
+    constexpr int kStage = std::is_same<T, bf16_t>::value ? kGroupTokens : 0;
+    qk_logits<T, D, G, kStage>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok, [&](int jb) { return c0 + jb; },
+                       [&](int jb) { return s_phys[jb]; }, s_p, ld, s_stage);
+    __syncthreads();
+    softmax_stats<G>(s_p, ld, ntok, a.b, nblk, s_m, s_l, s_bmp);
+    for (int pair = threadIdx.x; pair < G * nblk; pair += kAttnThreads) {
+      const int h = pair / nblk, jb = pair - h * nblk;
+      a.cal_bmp[((size_t)inst * G + h) * a.nb_cap + c0 + jb] = s_bmp[pair];
+    }
+    if (threadIdx.x < G) {
+      float* ml = a.cal_ml + (((size_t)inst * a.chunk_slots + chunk) * G + threadIdx.x) * 2;
+      ml[0] = s_m[threadIdx.x];
+      ml[1] = s_l[threadIdx.x];
+    }
+    __syncthreads();                                     // the next unit overwrites s_unit and the tiles
   }
 }
 
@@ -189,7 +205,11 @@ template <typename T, int D, int G>
 hipError_t run_calib(const Shape& s, CalibArgs a, hipStream_t st) {
   const size_t stage = std::is_same<T, bf16_t>::value ? 4 + k_stage_floats<D>() : 0;     // + alignment slack
   const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G + a.chunk_blocks + stage);
-  calibrate_kernel<T, D, G><<<dim3(a.n_chunks, s.n_inst), kAttnThreads, lds, st>>>(a);
+  if (s.calib_slots < 0) s.calib_slots = resident_workgroups(calibrate_kernel<T, D, G>, kAttnThreads, lds);
+  a.n_units = a.n_chunks * s.n_inst;
+  const int slots = s.calib_slots > 0 ? s.calib_slots : 2048;
+  zero_counter_kernel<<<1, 1, 0, st>>>(a.counter);
+  calibrate_kernel<T, D, G><<<dim3(a.n_units < slots ? a.n_units : slots), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   calibrate_finish_kernel<G><<<dim3(s.n_inst), kAttnThreads, sizeof(float) * a.n_chunks * G, st>>>(a);
@@ -238,6 +258,7 @@ hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_
   const WsLayout wl = ws_layout(s);
   CalibArgs a;
   a.q = q; a.K = K; a.row = row; a.cal_ml = ws + wl.cal_ml; a.cal_bmp = ws + wl.cal_bmp;
+  a.counter = reinterpret_cast<int*>(ws + wl.counters);
   a.t_cap = s.t_cap; a.nb_cap = s.nb_cap; a.b = s.b; a.log2b = ilog2(s.b); a.t_cur = t_cur;
   a.nb_cur = (t_cur + s.b - 1) / s.b;
   a.chunk_blocks = kCalibChunkTokens / s.b;
