@@ -263,7 +263,8 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
     finish_column<IW>(s_red, tid, (size_t)inst * nb_cap + c0 + tid, advance, W.b3[0], H, pstate, pred);
 }
 
-__global__ __launch_bounds__(256) void predict_inc_mfma_kernel(const float* __restrict__ hist,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4)))   // four workgroups per CU: 128 VGPRs
+void predict_inc_mfma_kernel(const float* __restrict__ hist,
                                                                const float* __restrict__ wts_global, int R, int H,
                                                                int newest_slot, int nb_cur, int nb_cap, int inst0,
                                                                int advance, float* __restrict__ pstate,

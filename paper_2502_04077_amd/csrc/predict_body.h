@@ -142,6 +142,7 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
 #pragma unroll
   for (int j = 0; j < 4; ++j) w3v[j] = wts_global[10 * C + 9 * C * C + C + 4 * hsel + j] * (1.f / kAccScale);
   const float b3 = wts_global[10 * C + 9 * C * C + 2 * C];
+  const float inv_H = 1.f / (float)H;                     // the time mean as a multiplication
   // layer-1 K slot e of this lane is (x row, kw) = divmod(8 hsel + e, 3); slot 15 has zero weights
   int xoff[8];
 #pragma unroll
@@ -158,7 +159,8 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
 #pragma unroll
   for (int i = 0; i < 5; ++i) {
     const int rr = hf + 2 * i;
-    xrow_off[i] = ring_slot(newest_slot, H, R, rr < 5 ? rr - 1 : H - 10 + rr) * nb_cap;
+    // (the same for the whole wave: kept scalar, so that the loads take a scalar base and a 32-bit lane offset)
+    xrow_off[i] = __builtin_amdgcn_readfirstlane(ring_slot(newest_slot, H, R, rr < 5 ? rr - 1 : H - 10 + rr) * nb_cap);
   }
   float xpre[5], pst_cur = 0.f, pst_next = 0.f;
   // Loads are unconditional on clamped addresses (no divergent branches); the raw values stay untouched in
@@ -166,9 +168,12 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
   auto fetch = [&](int tile, float& pst) __attribute__((always_inline)) {
     const int c0 = tile * IW;
     const int j = min(max(c0 + xcol, 0), nb_cur - 1);
+    const unsigned jb = (unsigned)j * 4u;               // byte offsets of 32 bits off scalar bases
 #pragma unroll
-    for (int i = 0; i < 5; ++i) xpre[i] = hist_inst[xrow_off[i] + j];
-    pst = pstate_inst[min(c0 + tid, nb_cur - 1)];
+    for (int i = 0; i < 5; ++i)
+      xpre[i] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(hist_inst + xrow_off[i]) + jb);
+    pst = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pstate_inst) +
+                                          (unsigned)min(c0 + tid, nb_cur - 1) * 4u);
   };
   auto stash = [&](int tile, uint32_t* s_x) __attribute__((always_inline)) {
     const int j = tile * IW + xcol;
@@ -251,9 +256,9 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
       float st = pst_cur;
       if (advance) {
         st = (st - part(0, 0)) + part(1, 0);
-        pstate_inst[c0 + tid] = st;
+        pstate_inst[(unsigned)(c0 + tid)] = st;
       }
-      pred_inst[c0 + tid] = b3 + (st + (part(0, 1) + part(1, 1))) / (float)H;
+      pred_inst[(unsigned)(c0 + tid)] = b3 + (st + (part(0, 1) + part(1, 1))) * inv_H;
     }
     if (more) stash(tile + 1, s_xb + (((tile - t_begin) & 1) ^ 1) * XBUF);
     pst_cur = pst_next;
