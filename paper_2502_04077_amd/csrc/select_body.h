@@ -17,7 +17,7 @@ namespace {
 constexpr int kSelThreads = 256;           // workgroup size of the common variant
 constexpr int kSelThreadsWide = 1024;      // few instances, long rows: more threads per instance
 constexpr int kSelBins = 256;              // radix of one pass; the first kSelBins threads own one bin each
-template <int NT> constexpr int sel_scratch_words() { return kSelBins + 3 * (NT / kWave) + 4; }
+template <int NT> constexpr int sel_scratch_words() { return kSelBins + 3 * (NT / kWave) + 8; }
 
 __device__ __forceinline__ uint32_t score_key(float x) {
   uint32_t u = __float_as_uint(x);
@@ -29,18 +29,34 @@ __device__ __forceinline__ uint32_t score_key(float x) {
 // so most lanes of a wave share a bin and per-lane LDS atomics would serialise on it: the two most common
 // leading bins are counted with a ballot and added once per wave, the rest fall back to single adds.
 __device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool active) {
-  const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
   for (int round = 0; round < 2; ++round) {
-    const unsigned long long live = __ballot(active);
-    if (live == 0) return;
-    const int leader = __ffsll((long long)live) - 1;
-    const uint32_t b0 = (uint32_t)__shfl((int)bin, leader, kWave);
-    const unsigned long long same = __ballot(active && bin == b0);
-    if (lane == leader) atomicAdd(&hist[b0], (uint32_t)__popcll(same));
-    if (bin == b0) active = false;
+    if (active) {                                       // (the lanes still to be counted are the ones executing here)
+      const uint32_t b0 = __builtin_amdgcn_readfirstlane(bin);          // bin of the first of them
+      const bool same = bin == b0;
+      const unsigned long long m = __ballot(same);
+      const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+      if (same && before == 0) atomicAdd(&hist[b0], (uint32_t)__popcll(m));
+      if (same) active = false;
+    }
   }
   if (active) atomicAdd(&hist[bin], 1u);
+}
+
+// Inclusive prefix sum over the 64 lanes with DPP moves (shifts within the rows of 16 lanes, then the last lane of
+// row 0 / 2 added to row 1 / 3 and the last lane of row 1 to rows 2 and 3): register moves, no trip through the LDS
+// permute path.  Every lane must be active.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+}
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  v += dpp_u32<0x111, 0xF>(v);                          // row_shr:1 (zero shifted in at the start of a row)
+  v += dpp_u32<0x112, 0xF>(v);                          // row_shr:2
+  v += dpp_u32<0x114, 0xF>(v);                          // row_shr:4
+  v += dpp_u32<0x118, 0xF>(v);                          // row_shr:8
+  v += dpp_u32<0x142, 0xA>(v);                          // row_bcast:15 into rows 1 and 3
+  v += dpp_u32<0x143, 0xC>(v);                          // row_bcast:31 into rows 2 and 3
+  return v;
 }
 
 // Selection for one instance by one workgroup of NT threads (a multiple of kSelBins).
@@ -55,8 +71,8 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
   uint32_t* s_wsum = s_mem + kSelBins;          // [kSelWaves]
   uint32_t* s_wgt = s_wsum + kSelWaves;         // [kSelWaves]
   uint32_t* s_weq = s_wgt + kSelWaves;          // [kSelWaves]
-  uint32_t& s_bin = s_mem[kSelBins + 3 * kSelWaves];
-  uint32_t& s_above = s_mem[kSelBins + 3 * kSelWaves + 1];
+  uint32_t* s_found = s_mem + kSelBins + 3 * kSelWaves; // [4 passes][bin, keys above it]: a slot per pass, so no
+                                                        // barrier is needed before the next pass may write
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
 
   if (nb_cur <= k) {                                    // everything fits the budget
@@ -86,9 +102,9 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
   uint32_t prefix = 0;                                  // high bits of T found so far
   uint32_t need = (uint32_t)k_mid;                      // still to take among keys matching prefix
   if (k_mid > 0) {
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      if (tid < kSelBins) s_hist[tid] = 0;
-      __syncthreads();
+    if (tid < kSelBins) s_hist[tid] = 0;
+    __syncthreads();
+    for (int shift = 24, pass = 0; shift >= 0; shift -= 8, ++pass) {
 #pragma unroll NK
       for (int i = 0; i < n_iter; ++i) {                   // uniform trip count: ballots need every lane
         const int j = lo + i * kSelThreads + tid;
@@ -102,12 +118,8 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
       uint32_t c = 0, incl = 0;
       if (tid < kSelBins) {
         c = s_hist[kSelBins - 1 - tid];
-        incl = c;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-          const uint32_t up = __shfl_up(incl, o, kWave);
-          if (lane >= o) incl += up;
-        }
+        s_hist[kSelBins - 1 - tid] = 0;                 // for the next pass, whose adds come two barriers later
+        incl = wave_incl_scan(c);
         if (lane == kWave - 1) s_wsum[wave] = incl;
       }
       __syncthreads();
@@ -116,12 +128,11 @@ __device__ __forceinline__ void select_topk_body(const float* __restrict__ p, in
         for (int w = 0; w < wave; ++w) base += s_wsum[w];
         incl += base;                                   // keys in bins >= 255 - tid
         const uint32_t excl = incl - c;                 // keys in bins >  255 - tid
-        if (excl < need && need <= incl) { s_bin = kSelBins - 1 - tid; s_above = excl; }
+        if (excl < need && need <= incl) { s_found[2 * pass] = kSelBins - 1 - tid; s_found[2 * pass + 1] = excl; }
       }
       __syncthreads();
-      prefix = (prefix << 8) | s_bin;
-      need -= s_above;
-      __syncthreads();
+      prefix = (prefix << 8) | s_found[2 * pass];
+      need -= s_found[2 * pass + 1];
     }
   }
   const uint32_t T = prefix;
