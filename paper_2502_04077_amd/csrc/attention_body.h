@@ -64,15 +64,30 @@ template <int LPT> __device__ __forceinline__ float lane_group_sum(float v) {
   return v;
 }
 
+// Reductions over the 64 lanes on DPP moves - shifts within the rows of 16 lanes, then the last lane of row 0 / 2
+// combined into row 1 / 3 and the last lane of row 1 into rows 2 and 3 - so that lane 63 holds the result, which a
+// scalar read hands to every lane: register moves instead of six trips through the LDS permute path.  Every lane
+// must be active.  FILL is the value shifted in at a row's start and kept by rows a step does not address.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_fill(float fill, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(fill), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_fill<0x111, 0xF>(-INFINITY, v));     // row_shr:1
+  v = fmaxf(v, dpp_fill<0x112, 0xF>(-INFINITY, v));     // row_shr:2
+  v = fmaxf(v, dpp_fill<0x114, 0xF>(-INFINITY, v));     // row_shr:4
+  v = fmaxf(v, dpp_fill<0x118, 0xF>(-INFINITY, v));     // row_shr:8
+  v = fmaxf(v, dpp_fill<0x142, 0xA>(-INFINITY, v));     // row_bcast:15 into rows 1 and 3
+  v = fmaxf(v, dpp_fill<0x143, 0xC>(-INFINITY, v));     // row_bcast:31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_fill<0x111, 0xF>(0.f, v);
+  v += dpp_fill<0x112, 0xF>(0.f, v);
+  v += dpp_fill<0x114, 0xF>(0.f, v);
+  v += dpp_fill<0x118, 0xF>(0.f, v);
+  v += dpp_fill<0x142, 0xA>(0.f, v);
+  v += dpp_fill<0x143, 0xC>(0.f, v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));
 }
 
 template <typename T, int D, int G> struct Geom {
@@ -261,10 +276,7 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
     }
   }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-#pragma unroll
-    for (int j = 0; j < HPW; ++j) m[j] = fmaxf(m[j], __shfl_xor(m[j], o, 64));
-  }
+  for (int j = 0; j < HPW; ++j) m[j] = wave_max(m[j]);   // (independent chains: the compiler interleaves them)
   if (s_alpha != nullptr) {
 #pragma unroll
     for (int j = 0; j < HPW; ++j) {
@@ -299,10 +311,7 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
     }
   }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-#pragma unroll
-    for (int j = 0; j < HPW; ++j) sum[j] += __shfl_xor(sum[j], o, 64);
-  }
+  for (int j = 0; j < HPW; ++j) sum[j] = wave_sum(sum[j]);
   if (lane == 0) {
 #pragma unroll
     for (int j = 0; j < HPW; ++j) {
@@ -407,12 +416,13 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     int mine = 0;
     for (int i = 0; i < per_lane; ++i)
       if (w0 + i < nwords) mine += __popc(s_listed[w0 + i]);
-    int incl = mine;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-      const int up = __shfl_up(incl, o, kWave);
-      if (lane >= o) incl += up;
-    }
+    int incl = mine;                                   // inclusive prefix sum over the lanes, on DPP moves
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xF, 0xF, true);   // row_shr:1
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xF, 0xF, true);   // row_shr:2
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xF, 0xF, true);   // row_shr:4
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xF, 0xF, true);   // row_shr:8
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x142, 0xA, 0xF, true);   // row_bcast:15 into rows 1 and 3
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x143, 0xC, 0xF, true);   // row_bcast:31 into rows 2 and 3
     int run = incl - mine;
     for (int i = 0; i < per_lane; ++i)
       if (w0 + i < nwords) { s_rank[w0 + i] = run; run += __popc(s_listed[w0 + i]); }
