@@ -220,6 +220,10 @@ ATTN_CASES = [
     ("many-inst", dict(kv_heads=8, batch=160, g=4, head_dim=128, budget_tokens=256, t0=600), 600),
     ("many-inst-k64", dict(kv_heads=8, batch=130, g=4, head_dim=128, budget_tokens=1024, t0=1100), 1099),
     ("big-budget", dict(kv_heads=2, g=4, head_dim=128, budget_tokens=4096, t0=9000), 8999),
+    # more instances than the chip holds four-wave workgroups: the pieced two-wave form (pieces of 32 + 16 blocks)
+    # and, with g = 1 and 4096 instances, the one-wave form
+    ("two-wave", dict(kv_heads=8, batch=200, g=4, head_dim=128, budget_tokens=768, t0=1100), 1093),
+    ("one-wave", dict(kv_heads=16, batch=256, g=1, head_dim=128, budget_tokens=640, t0=900), 899),
 ]
 
 
@@ -261,8 +265,9 @@ def test_sparse_decode_vs_oracle(name, kw, t_cur):
 
 
 @pytest.mark.parametrize("kw", [dict(kv_heads=6, g=4, head_dim=128, budget_tokens=512, t0=3000),
-                                dict(kv_heads=8, batch=130, g=4, head_dim=128, budget_tokens=256, t0=600)],
-                         ids=["split", "whole"])
+                                dict(kv_heads=8, batch=130, g=4, head_dim=128, budget_tokens=256, t0=600),
+                                dict(kv_heads=8, batch=200, g=4, head_dim=128, budget_tokens=1024, t0=1100)],
+                         ids=["split", "whole", "two-wave"])
 def test_sparse_decode_ragged_counts(kw):
     """Lists shorter than the budget, one of them empty; the idx entries past cnt are garbage and must be ignored.
     An empty list gives a zero output and a zero row."""
@@ -561,8 +566,10 @@ def _paged_copy(w, run, K, V, dev, seed=3):
 
 
 @pytest.mark.parametrize("kw", [dict(kv_heads=3, t0=3000, budget_tokens=1024), dict(kv_heads=8, batch=130, t0=700),
-                                dict(kv_heads=2, g=1, t0=1500, kv_dtype="f32", head_dim=64)],
-                         ids=["split", "one-wg-per-instance", "f32"])
+                                dict(kv_heads=2, g=1, t0=1500, kv_dtype="f32", head_dim=64),
+                                # more instances than resident four-wave workgroups: the two-wave, pieced form
+                                dict(kv_heads=8, batch=200, t0=1100, budget_tokens=768)],
+                         ids=["split", "one-wg-per-instance", "f32", "two-wave"])
 def test_paged_kv_equals_contiguous(kw):
     """A block table that scatters the cache over a pool changes addresses only: same bytes out."""
     dev = _dev()
