@@ -24,6 +24,11 @@
  *   - Calls return AP_OK or a negative error code; an error found on the host leaves all outputs
  *     untouched.  No call throws.  Only ap_create / ap_set_weights / ap_destroy allocate or free
  *     (ap_offload_begin creates two events on its first call).
+ *   - The first attention call of a context (ap_sparse_decode, ap_calibrate, ap_step and the offload calls)
+ *     asks the runtime once how many of its workgroups the device holds at a time; it is a host query,
+ *     nothing is enqueued for it, but make that first call outside a stream capture.
+ *   - Calls that use one context or one workspace are issued in stream order on one stream: the workspace
+ *     (partial results, the work counter of the calibration kernel) is shared by them.
  *   - All instances share one length t_cur per call.
  *   - Inputs must be finite; NaN scores give an unspecified (but in-range, duplicate-free) selection.
  */
