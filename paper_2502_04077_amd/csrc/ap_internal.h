@@ -13,6 +13,7 @@ constexpr int kWave = 64;
 constexpr int kAttnThreads = 256;             // 4 waves per attention workgroup
 constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kNarrowPieceTokens = 512;       // tokens whose probabilities a two- or one-wave sparse-decode workgroup holds in LDS at a time
+constexpr int kMaxHist = 256;                 // longest history ap_create accepts
 constexpr int kGroupTokens = 16;              // tokens one wave covers per load group (4 x dwordx4 loads)
 constexpr int kCalibChunkTokens = 1024;       // tokens per calibration workgroup
 

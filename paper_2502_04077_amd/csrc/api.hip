@@ -72,7 +72,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   if (c->g != 1 && c->g != 2 && c->g != 4 && c->g != 8) return AP_ERR_UNSUPPORTED;
   if (c->head_dim != 64 && c->head_dim != 128) return AP_ERR_UNSUPPORTED;
   if (c->kv_dtype != AP_F32 && c->kv_dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
-  if (c->hist_len > 256) return AP_ERR_UNSUPPORTED;
+  if (c->hist_len > ap::kMaxHist) return AP_ERR_UNSUPPORTED;
   if (c->k_blocks > 16384) return AP_ERR_UNSUPPORTED;
   const bool chan_ok = (c->c1 == 4 && c->c2 == 4) || (c->c1 == 8 && c->c2 == 8) || (c->c1 == 16 && c->c2 == 32);
   if (!chan_ok) return AP_ERR_UNSUPPORTED;

@@ -303,8 +303,10 @@ __global__ __launch_bounds__(256) void predict_interior_mfma16_kernel(const floa
 }
 
 // Full evaluation of a few columns (the ones whose state is void after the tile has grown by a block):
-// one wave per (instance, column), lanes are time rows.  A lane gathers the 5 x 5 x neighbourhood of its
-// pixel from the ring and evaluates y1 on the 3 x 3 pixels around it channel by channel, feeding y2.
+// one wave per (instance, column), lanes are time rows.  A lane fetches the five x values of its own row (one
+// 32-byte sector of the ring) into LDS, takes the 5 x 5 neighbourhood of its pixel from there (the rows above
+// and below were fetched by the neighbouring lanes) and evaluates y1 on the 3 x 3 pixels around it channel by
+// channel, feeding y2.
 template <int C1, int C2>
 __global__ __launch_bounds__(kWave) void predict_columns_kernel(const float* __restrict__ hist,
                                                                 const float* __restrict__ wts_global, int R, int H,
@@ -316,21 +318,26 @@ __global__ __launch_bounds__(kWave) void predict_columns_kernel(const float* __r
   const int j = col_begin + blockIdx.x;
   const int lane = threadIdx.x;
   const float* hist_inst = hist + (size_t)inst * R * nb_cap;
+  __shared__ float s_x[(kMaxHist + 4) * 5];              // rows -2 .. H + 1 of columns j - 2 .. j + 2, zero outside the tile
+  for (int r = lane; r < H + 4; r += kWave) {
+    const int rr = r - 2;
+    const bool row_ok = rr >= 0 && rr < H;
+    const float* src = hist_inst + (size_t)ring_slot(newest_slot, H, R, row_ok ? rr : 0) * nb_cap;
+#pragma unroll
+    for (int dc = 0; dc < 5; ++dc) {
+      const int jj = j - 2 + dc;
+      const float v = src[min(max(jj, 0), nb_cur - 1)];
+      s_x[r * 5 + dc] = (row_ok && jj >= 0 && jj < nb_cur) ? v : 0.f;
+    }
+  }
+  __syncthreads();
   float w_int = 0.f, w_bor = 0.f;
   for (int r = lane; r < H; r += kWave) {
     float x[5][5];
 #pragma unroll
-    for (int dr = 0; dr < 5; ++dr) {
-      const int rr = r - 2 + dr;
-      const bool row_ok = rr >= 0 && rr < H;
-      const float* src = hist_inst + (size_t)ring_slot(newest_slot, H, R, row_ok ? rr : 0) * nb_cap;
+    for (int dr = 0; dr < 5; ++dr)
 #pragma unroll
-      for (int dc = 0; dc < 5; ++dc) {
-        const int jj = j - 2 + dc;
-        const float v = src[min(max(jj, 0), nb_cur - 1)];
-        x[dr][dc] = (row_ok && jj >= 0 && jj < nb_cur) ? v : 0.f;
-      }
-    }
+      for (int dc = 0; dc < 5; ++dc) x[dr][dc] = s_x[(r + dr) * 5 + dc];
     float acc[C2];
 #pragma unroll
     for (int c = 0; c < C2; ++c) acc[c] = W.b2[c];
