@@ -18,9 +18,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the
-# same counters read for ap_stream_copy of known size (summaries under profiles/); GB per launch.
-MEASURED_TRAFFIC_GB = {("cfg2", "sparse_decode"): 1.0977}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the
+# same counters read for ap_stream_copy of known size: one line per (kernel, workload, instances) in this table,
+# written from the summaries beside it.  A kernel and shape the table does not hold reports `null`.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+
+
+def measured_traffic_gb(kernel, workload, n_inst):
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 4 and not line.startswith("#") and parts[0] == kernel and parts[1] == workload \
+                        and int(parts[2]) == n_inst:
+                    return float(parts[3])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def algorithmic_bytes(w, t):
@@ -49,23 +63,21 @@ def algorithmic_flops(w, t):
     }
 
 
-def cpu_baseline(w, run, K, V, budget_s=20.0, max_inst=16):
+def cpu_baseline(w, hist, dev, K, V, budget_s=20.0, max_inst=16):
     """Times the oracle's decode_step as it stands on a bounded sample of instances."""
     import numpy as np
     import torch
     from oracle import attnpred_oracle as orc
     from workloads import predictor_weights, queries, to_f64
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = 1
+        cores = len(os.sched_getaffinity(0))               # host cores this process may run on
+    except AttributeError:
+        cores = os.cpu_count() or 1
     wts = orc.PredictorWeights.from_blob(predictor_weights(w), w.c1, w.c2)
-    hist = run.logical_history()
     t = w.t_at(0)
-    q = queries(w, 0, run.dev)
+    q = queries(w, 0, dev)
     n_done, t_used = 0, 0.0
-    for i in range(min(max_inst, w.n_inst)):
+    for i in range(min(max_inst, w.n_inst, hist.shape[0])):
         h = hist[i].cpu().numpy().astype(np.float64)
         qi, Ki, Vi = to_f64(q[i]), to_f64(K[i]), to_f64(V[i])
         t0 = time.perf_counter()
@@ -79,7 +91,9 @@ def cpu_baseline(w, run, K, V, budget_s=20.0, max_inst=16):
     return {
         "value": 1.0 / (per_inst * w.n_inst), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
         "sample": f"{n_done} of {w.n_inst} instances x 1 non-calibration decode step of {w.name}, "
-                  f"{per_inst * 1e3:.1f} ms per instance-step, extrapolated to all instances",
+                  f"{per_inst * 1e3:.1f} ms per instance-step, extrapolated to all instances; the oracle is numpy "
+                  f"float64 with Python loops over the kernel taps: one thread except inside its matrix products, "
+                  f"which may use the BLAS pool on the cores counted",
     }
 
 
@@ -236,9 +250,7 @@ def main():
     qs = [q[nd:] for q in qs_all]
     torch.cuda.synchronize()
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(w, run, K, V)
+    hist0 = run.logical_history()[: min(16, w.n_inst)].clone()   # the CPU baseline (below) starts from this history
 
     modes = []
 
@@ -258,6 +270,12 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     n_calib = sum(1 for s in range(args.warmup, total_steps) if w.is_calibration_step(s))
     n_rebase = sum(modes)
+
+    # The oracle on the host cores, after the timed region: the GPU idles meanwhile, and a timed region right
+    # after an idle spell starts at low clocks.
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, hist0, run.dev, K, V)
 
     # Per-call durations with events on the launch stream, replaying the same steps un-fused.
     kern_ms = {}
@@ -289,6 +307,12 @@ def main():
                 timed("calibrate", lambda: run.ctx.calibrate(qs[s], K, t, run.row, run.ws))
             timed("update_history", lambda: run.ctx.update_history(run.hist, run.n_pushed, run.row))
             run.n_pushed += 1
+        calib_outside = "calibrate" not in marks
+        if calib_outside:                                  # no calibration step fell into the replayed steps: time one
+            t_c = w.t_at(total_steps - 1)
+            run.ctx.calibrate(qs[-1], K, t_c, run.row, run.ws)
+            for _ in range(2):
+                timed("calibrate", lambda: run.ctx.calibrate(qs[-1], K, t_c, run.row, run.ws))
         torch.cuda.synchronize()
         for n, m in marks.items():
             kern_ms[n] = sum(a.elapsed_time(b) for a, b in m) / len(m)
@@ -341,7 +365,7 @@ def main():
         dom = max(per_step, key=per_step.get)
         ach = ab[dom] * w.n_inst / (kern_ms[dom] * 1e-3) / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_GB.get((w.name, dom)),
+                    "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic_gb(dom, w.name, w.n_inst),
                     "avg_launch_ms": kern_ms[dom], "algorithmic_GB_per_launch": ab[dom] * w.n_inst / 1e9,
                     "measured_read_ceiling_GBs": ceiling_gbs, "frac_of_measured_ceiling": ach / ceiling_gbs}
         roofline["other_kernels"] = {
@@ -350,6 +374,7 @@ def main():
             for k in ("calibrate", "predict_incremental", "select") if k in kern_ms and k != dom}
     step_bytes = (ab["predict_incremental"] + ab["select"] + ab["sparse_decode"]) * w.n_inst
     timed_bytes = step_bytes * args.steps + ab["calibrate"] * w.n_inst * n_calib + ab["predict_full"] * w.n_inst * n_rebase
+    mfma = run.ctx.cfg.flags == 0 and (w.c1, w.c2) in ((8, 8), (16, 32))
     out = {
         "metric": "predict+top-k+sparse-attn decode steps/s at 32K ctx; % HBM peak",
         "value": 1e3 / ms_per_step, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -360,12 +385,18 @@ def main():
                    "block": w.block, "history": w.hist_len, "budget_tokens": w.budget_tokens,
                    "predictor_channels": [w.c1, w.c2], "calibration_every": w.calib_every,
                    "calibration_steps_in_timed_region": n_calib, "predictor": "incremental",
+                   "predictor_arith": ("f16 MFMA operands (history and first-layer maps as differences from the "
+                                       "all-zero-history response), fp32 accumulate" if mfma else "fp32 FMA"),
                    "predictor_rebase_every": run.rebase_every, "rebase_steps_in_timed_region": n_rebase,
                    "selection_refresh_every": args.refresh_every, "dense_layers": args.dense_layers},
-        # algorithmic bytes of everything in the timed region (steps, calibrations, re-bases) over its wall time
-        "step_hbm_frac": timed_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
-        "step_algorithmic_GB": timed_bytes / args.steps / 1e9,
+        # the per-step calls only (predict + select + sparse decode): their algorithmic bytes over the wall time of
+        # the whole timed region, whatever else ran in it ...
+        "step_hbm_frac": step_bytes * args.steps / elapsed / 1e9 / HBM_PEAK_GBS,
+        "step_algorithmic_GB": step_bytes / 1e9,
+        # ... and with the bytes of the calibrations and re-bases that fell into the region counted as well
+        "step_hbm_frac_with_calibration": timed_bytes / elapsed / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,
+        "calibrate_timed_outside_region": bool(kern_ms) and calib_outside,
         # the same attention kernel over every block of the context (all instances), and what the budget saves
         "dense_attention": None if dense_ms is None else {
             "ms": dense_ms, "GBs": 2 * w_all.n_inst * t_mid * w_all.head_dim * (2 if w_all.kv_dtype == "bf16" else 4) / dense_ms / 1e6,

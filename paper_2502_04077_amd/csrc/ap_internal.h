@@ -25,13 +25,18 @@ constexpr int kCalibChunkTokens = 1024;       // tokens per calibration workgrou
 //   b2[c2]                     at 10*c1 + 9*c1*c2
 //   w3[c2]                     at 10*c1 + 9*c1*c2 + c2
 //   b3                         at 10*c1 + 9*c1*c2 + 2*c2
+// What the runtime says the device holds at once (asked at the first launch that needs it).  Lives in the
+// context; a Shape points at it, so that copies of a Shape (the offload calls make two) share the answers.
+struct Occupancy {
+  int sparse_slots[3] = {-1, -1, -1};   // sparse-decode workgroups in the four-, two- and one-wave form
+  int calib_slots = -1;                 // calibration workgroups
+};
+
 struct Shape {
   int n_inst, g, d, b, H, R, t_cap, nb_cap, k, n_sink, n_local, c1, c2, kv_dtype;
   int predictor_mfma; // incremental predictor on f16 MFMA (8/8 and 16/32 channels)
   int n_split;        // workgroups per instance in sparse decode
-  // sparse-decode workgroups the device holds at once in the four-, two- and one-wave form (found at the first launch)
-  mutable int sparse_slots[3] = {-1, -1, -1};
-  mutable int calib_slots = -1;   // calibration workgroups the device holds at once
+  Occupancy* occ;     // owned by the context, never null
   int calib_chunks;   // max workgroups per instance in calibrate
   const int32_t* table;  // device block table of a paged K/V cache [n_inst][nb_cap], or null (caller-owned)
   int n_phys;            // physical blocks in the pool

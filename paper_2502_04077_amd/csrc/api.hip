@@ -11,7 +11,7 @@ struct ap_ctx {
   // ap_offload_*: "selection for the next token is written" / "its blocks are staged"; created on first use, owned
   hipEvent_t ev_selected, ev_staged;
   bool have_events;
-  const void* readable[2];   // the last two pointers check_device_readable accepted (the K and V caches)
+  ap::Occupancy occ;         // what the device holds at once; s.occ points here
 };
 
 namespace ap {
@@ -81,6 +81,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   ap_ctx* ctx = new (std::nothrow) ap_ctx;
   if (ctx == nullptr) return AP_ERR_ARG;
   Shape& s = ctx->s;
+  s.occ = &ctx->occ;
   s.n_inst = c->n_inst; s.g = c->g; s.d = c->head_dim; s.b = c->block; s.H = c->hist_len;
   s.R = c->hist_len + 1; s.t_cap = c->t_cap; s.nb_cap = c->t_cap / c->block; s.k = c->k_blocks;
   s.n_sink = c->n_sink; s.n_local = c->n_local; s.c1 = c->c1; s.c2 = c->c2; s.kv_dtype = c->kv_dtype;
@@ -103,7 +104,6 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   ctx->dweights = nullptr;
   ctx->have_weights = false;
   ctx->have_events = false;
-  ctx->readable[0] = ctx->readable[1] = nullptr;
   *out = ctx;
   return AP_OK;
 }
@@ -394,21 +394,17 @@ int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, i
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
-// A pointer a kernel may read: device memory, or host memory that is pinned and mapped.  Pageable
-// host memory would fault the GPU, so it is refused here.  The answer for the last two accepted pointers is
-// remembered: a decode loop passes the same two caches on every call.
-static int check_device_readable(ap_ctx* ctx, const void* p) {
-  if (p == ctx->readable[0] || p == ctx->readable[1]) return AP_OK;
+// A pointer a kernel may read: device memory, or host memory that is pinned and mapped.  Pageable host memory
+// would fault the GPU, so it is refused here.  The runtime is asked on every call: an answer remembered from an
+// earlier call could outlive the buffer it was given for.
+static int check_device_readable(const void* p) {
   hipPointerAttribute_t a;
   if (hipPointerGetAttributes(&a, p) != hipSuccess) {
     (void)hipGetLastError();
     return AP_ERR_ARG;
   }
   const bool ok = a.type == hipMemoryTypeHost || a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged;
-  if (!ok) return AP_ERR_ARG;
-  ctx->readable[1] = ctx->readable[0];
-  ctx->readable[0] = p;
-  return AP_OK;
+  return ok ? AP_OK : AP_ERR_ARG;
 }
 
 int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float* row, void* ws, void* stream) {
@@ -416,7 +412,7 @@ int ap_calibrate(ap_ctx* ctx, const void* q, const void* K, int32_t t_cur, float
   AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(row); AP_REQUIRE_PTR(ws);
   const Shape& s = ctx->s;
   if (t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
-  if (check_device_readable(ctx, K) != AP_OK) return AP_ERR_ARG;
+  if (check_device_readable(K) != AP_OK) return AP_ERR_ARG;
   hipError_t e = ap::launch_calibrate(s, q, K, t_cur, row, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
@@ -480,7 +476,7 @@ int ap_prefetch_blocks(ap_ctx* ctx, const void* K_src, const void* V_src, int32_
   const Shape& s = ctx->s;
   if (s.k > 256) return AP_ERR_UNSUPPORTED;
   if (nb_cur < 1 || nb_cur > s.nb_cap || t_avail < 0 || t_avail > s.t_cap) return AP_ERR_RANGE;
-  if (check_device_readable(ctx, K_src) != AP_OK || check_device_readable(ctx, V_src) != AP_OK) return AP_ERR_ARG;
+  if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
   hipError_t e = ap::launch_gather_blocks(s, K_src, V_src, t_avail, nb_cur, idx, cnt, pool_K, pool_V, block_table,
                                           state, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
@@ -541,7 +537,7 @@ int ap_offload_begin(ap_ctx* ctx, const float* hist, int64_t n_pushed, const voi
   if (!ctx->have_weights) return AP_ERR_STATE;
   if (s.n_local < 1 || s.k > 256) return AP_ERR_UNSUPPORTED;
   if (n_pushed < 0 || t_first < 1 || t_first > s.t_cap) return AP_ERR_RANGE;
-  if (check_device_readable(ctx, K_src) != AP_OK || check_device_readable(ctx, V_src) != AP_OK) return AP_ERR_ARG;
+  if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
   int rc = offload_events(ctx);
   if (rc != AP_OK) return rc;
   return offload_select_and_fetch(ctx, hist, n_pushed, K_src, V_src, t_first, t_first - 1, AP_PRED_REBASE, idx, cnt, pred,
@@ -563,7 +559,7 @@ int ap_offload_step(ap_ctx* ctx, float* hist, int64_t n_pushed, const void* q, c
   if (!ctx->have_weights || !ctx->have_events) return AP_ERR_STATE;      // ap_offload_begin comes first
   if (pred_mode != AP_PRED_REBASE && pred_mode != AP_PRED_ADVANCE) return AP_ERR_ARG;
   if (n_pushed < 0 || t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
-  if (check_device_readable(ctx, K_src) != AP_OK || check_device_readable(ctx, V_src) != AP_OK) return AP_ERR_ARG;
+  if (check_device_readable(K_src) != AP_OK || check_device_readable(V_src) != AP_OK) return AP_ERR_ARG;
   hipStream_t cs = static_cast<hipStream_t>(compute_stream), ps = static_cast<hipStream_t>(copy_stream);
   if (hipStreamWaitEvent(cs, ctx->ev_staged, 0) != hipSuccess) return AP_ERR_HIP;
   if (ap::launch_append_row(s, k_new, v_new, t_cur - 1, block_table, state, pool_K, pool_V, cs) != hipSuccess)

@@ -1,6 +1,7 @@
 // Kernels around attention_body.h: block-sparse decode (+ combine of splits) and dense calibration.
 #include "attention_body.h"
 
+
 namespace ap {
 namespace {
 
@@ -175,15 +176,15 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
     const int pb_n = kNarrowPieceTokens / a.b;
     const size_t lds_2 = sizeof(float) * sparse_lds_floats<D, G, 2>(nblk_cap, pb_n, a.b, a.nb_cap);
     const size_t lds_1 = sizeof(float) * sparse_lds_floats<D, G, 1>(nblk_cap, pb_n, a.b, a.nb_cap);
-    if (s.sparse_slots[0] < 0) {
-      s.sparse_slots[0] = resident_workgroups(sparse_decode_kernel<T, D, G, kAttnWaves, false>, kAttnThreads, lds);
-      s.sparse_slots[1] = resident_workgroups(sparse_decode_kernel<T, D, G, 2, true>, 2 * kWave, lds_2);
-      s.sparse_slots[2] = resident_workgroups(sparse_decode_kernel<T, D, G, 1, true>, kWave, lds_1);
+    if (s.occ->sparse_slots[0] < 0) {
+      s.occ->sparse_slots[0] = resident_workgroups(sparse_decode_kernel<T, D, G, kAttnWaves, false>, kAttnThreads, lds);
+      s.occ->sparse_slots[1] = resident_workgroups(sparse_decode_kernel<T, D, G, 2, true>, 2 * kWave, lds_2);
+      s.occ->sparse_slots[2] = resident_workgroups(sparse_decode_kernel<T, D, G, 1, true>, kWave, lds_1);
     }
     int form = 0, best_rounds = 0;
     for (int f = 0; f < 3; ++f) {
-      if (s.sparse_slots[f] <= 0) { form = 0; break; }     // occupancy unknown: stay with the four-wave form
-      const int rounds = (ninst + s.sparse_slots[f] - 1) / s.sparse_slots[f];
+      if (s.occ->sparse_slots[f] <= 0) { form = 0; break; }     // occupancy unknown: stay with the four-wave form
+      const int rounds = (ninst + s.occ->sparse_slots[f] - 1) / s.occ->sparse_slots[f];
       if (f == 0 || rounds < best_rounds) { form = f; best_rounds = rounds; }
     }
     if (form != 0) {
@@ -205,9 +206,9 @@ template <typename T, int D, int G>
 hipError_t run_calib(const Shape& s, CalibArgs a, hipStream_t st) {
   const size_t stage = std::is_same<T, bf16_t>::value ? 4 + k_stage_floats<D>() : 0;     // + alignment slack
   const size_t lds = sizeof(float) * ((size_t)G * a.chunk_blocks * a.b + G * a.chunk_blocks + 2 * G + a.chunk_blocks + stage);
-  if (s.calib_slots < 0) s.calib_slots = resident_workgroups(calibrate_kernel<T, D, G>, kAttnThreads, lds);
+  if (s.occ->calib_slots < 0) s.occ->calib_slots = resident_workgroups(calibrate_kernel<T, D, G>, kAttnThreads, lds);
   a.n_units = a.n_chunks * s.n_inst;
-  const int slots = s.calib_slots > 0 ? s.calib_slots : 2048;
+  const int slots = s.occ->calib_slots > 0 ? s.occ->calib_slots : 2048;
   zero_counter_kernel<<<1, 1, 0, st>>>(a.counter);
   calibrate_kernel<T, D, G><<<dim3(a.n_units < slots ? a.n_units : slots), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();

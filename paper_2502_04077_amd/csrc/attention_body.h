@@ -460,9 +460,13 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
 #pragma unroll
       for (int i = 0; i < NL; ++i) vw[i] = make_uint4(0, 0, 0, 0);
       if (tau0 < ntok) {
-        const int ptok0 = s_phys[p0 + (tau0 >> a.log2b)] * a.b + (tau0 & (a.b - 1));
+        // Tokens at or beyond t_cur (the tail of the newest block) carry probability 0, but their V rows may hold
+        // anything, NaN included, and 0 * NaN is NaN: such a token reads the block's last real row instead.
+        const int jb = p0 + (tau0 >> a.log2b), off = tau0 & (a.b - 1);
+        const int last = min(a.t_cur - 1 - s_idx[jb] * a.b, a.b - 1);   // >= 0: a listed block starts before t_cur
+        const int prow0 = s_phys[jb] * a.b;
 #pragma unroll
-        for (int i = 0; i < NL; ++i) vw[i] = ld_stream(V_inst + (size_t)(ptok0 + i) * D + dpart * E);
+        for (int i = 0; i < NL; ++i) vw[i] = ld_stream(V_inst + (size_t)(prow0 + min(off + i, last)) * D + dpart * E);
       }
     };
     if (kEarlyV && wave < ngroups) load_v(wave);

@@ -234,3 +234,51 @@ def test_decode_step_wiring():
             assert np.count_nonzero(r.row) == nb
         else:
             assert np.count_nonzero(r.row) == k
+
+
+def test_decode_step_reuse_branch_wiring():
+    """A step that does not update the positions (Sec. 3.3): the selection comes from the earlier step's list,
+    not from this step's scores.  Expectations are written out by hand for the case at hand: the context grew
+    from 16 to 18 blocks (t 128 -> 137 with b = 8) since the list was made, n_sink = 1, n_local = 2, k = 6.
+    Old list {0, 3, 7, 11, 14, 15}: 14 and 15 were the old local window and are dropped (neither is a sink),
+    0, 3, 7, 11 stay, the new local window {16, 17} joins: {0, 3, 7, 11, 16, 17} - although the scores of this
+    step (windowed mean of a history that peaks at blocks 5 and 9) would have picked 5 and 9."""
+    rng = np.random.default_rng(8)
+    g, d, t, b, H, k = 2, 8, 137, 8, 4, 6
+    nb = -(-t // b)
+    assert nb == 18
+    q, K, V = rng.standard_normal((g, d)), rng.standard_normal((t, d)), rng.standard_normal((t, d))
+    hist = 0.01 * rng.random((H, nb))
+    hist[:, 5] += 1.0
+    hist[:, 9] += 0.5
+    w = orc.PredictorWeights.from_blob(np.zeros(2 * 9 + 2 + 2 * 2 * 9 + 2 + 2 + 1), 2, 2)
+    w.w1[0, 1, 1] = w.w2[0, 0, 1, 1] = w.w3[0] = 1.0
+    old = np.array([0, 3, 7, 11, 14, 15])
+    expected = [0, 3, 7, 11, 16, 17]
+    fresh = orc.decode_step(hist, q, K, V, t, w, b=b, k=k, n_sink=1, n_local=2, calibrate=False)
+    assert {5, 9} <= set(fresh.blocks.tolist())                      # what predicting would have chosen
+    for calib in (False, True):
+        r = orc.decode_step(hist, q, K, V, t, w, b=b, k=k, n_sink=1, n_local=2, calibrate=calib, reuse=(old, 16))
+        assert r.blocks.tolist() == expected
+        np.testing.assert_allclose(r.pred, hist.sum(axis=0) / H, rtol=1e-13)   # the scores are still reported
+        # attention over exactly the tokens of the carried-over blocks, by the definition of Sec. 3.1
+        tok = np.concatenate([np.arange(j * b, min((j + 1) * b, t)) for j in expected])
+        logits = q @ K[tok].T / np.sqrt(d)
+        p = np.exp(logits - logits.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        np.testing.assert_allclose(r.out, p @ V[tok], rtol=1e-12, atol=1e-14)
+        np.testing.assert_array_equal(r.hist[:-1], hist[1:])
+        if calib:
+            assert np.count_nonzero(r.row) == nb
+        else:
+            assert sorted(np.nonzero(r.row)[0].tolist()) == expected
+            # pooled probabilities: per block the largest probability over tokens and heads
+            want = np.zeros(nb)
+            for j in expected:
+                sel = (tok // b) == j
+                want[j] = p[:, sel].max()
+            np.testing.assert_allclose(r.row, want, rtol=1e-12)
+    # a list made for the same width is used as it is
+    same = orc.decode_step(hist, q, K, V, t, w, b=b, k=k, n_sink=1, n_local=2, calibrate=False,
+                           reuse=(np.array(expected), nb))
+    assert same.blocks.tolist() == expected
