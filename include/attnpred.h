@@ -170,6 +170,19 @@ int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, i
                      const int32_t* idx, const int32_t* cnt, float* out, float* row, void* ws,
                      void* stream);
 
+/* ap_sparse_decode for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as ap_sparse_decode
+ * without `ws`: the split partials go to a static device array of AP_NOALLOC_SCRATCH_BYTES that the library keeps
+ * on every GPU it runs on (looked up once per device; nothing is allocated or freed here, nor by anything this
+ * calls).  A context whose partials need more (many instances with several workgroups each) is refused with
+ * AP_ERR_RANGE before anything is launched; contexts with one workgroup per instance need none.  All calls on one
+ * GPU share the array, whatever their context or stream: calls that overlap on one GPU race, issue them in
+ * stream order on one stream.  Nothing in the array has to start at zero (every word read was written by the same
+ * call). */
+#define AP_NOALLOC_SCRATCH_BYTES (4u << 20)
+int ap_sparse_decode_noalloc(ap_ctx* ctx, const void* q, const void* K, const void* V, int32_t t_cur,
+                             const int32_t* idx, const int32_t* cnt, float* out, float* row, void* stream);
+
 /* Distribution error calibration (Sec. 3.3): the pooled row of the dense attention of q over all
  * t_cur tokens.  Reads K only and produces no attention output.  K may also be pinned (mapped) host
  * memory, which the kernel then reads over PCIe; pageable host memory is refused with AP_ERR_ARG.

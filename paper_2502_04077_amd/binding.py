@@ -22,7 +22,7 @@ AP_OK, AP_ERR_ARG, AP_ERR_ALIGN, AP_ERR_RANGE, AP_ERR_HIP, AP_ERR_UNSUPPORTED, A
 
 EXPORTS = [
     "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_set_block_table",
-    "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_refresh_selection", "ap_sparse_decode", "ap_calibrate", "ap_update_history", "ap_step",
+    "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_refresh_selection", "ap_sparse_decode", "ap_sparse_decode_noalloc", "ap_calibrate", "ap_update_history", "ap_step",
     "ap_prefetch_state_bytes", "ap_prefetch_blocks", "ap_append_kv", "ap_offload_begin", "ap_offload_step", "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
 
@@ -68,6 +68,7 @@ def load_library() -> C.CDLL:
     lib.ap_select_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.ap_refresh_selection.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.ap_sparse_decode.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.ap_sparse_decode_noalloc.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.ap_calibrate.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     lib.ap_update_history.argtypes = [vp, vp, i64, vp, vp]
     lib.ap_step.argtypes = [vp, vp, i64, vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, vp, vp]
@@ -180,6 +181,10 @@ class Context:
     def sparse_decode(self, q, K, V, t_cur, idx, cnt, out, row, ws) -> None:
         _check(self._lib.ap_sparse_decode(self._h, _ptr(q), _ptr(K), _ptr(V), t_cur, _ptr(idx), _ptr(cnt),
                                           _ptr(out), _ptr(row), _ptr(ws), _stream()))
+
+    def sparse_decode_noalloc(self, q, K, V, t_cur, idx, cnt, out, row) -> None:
+        _check(self._lib.ap_sparse_decode_noalloc(self._h, _ptr(q), _ptr(K), _ptr(V), t_cur, _ptr(idx), _ptr(cnt),
+                                                  _ptr(out), _ptr(row), _stream()))
 
     def calibrate(self, q, K, t_cur, row, ws) -> None:
         _check(self._lib.ap_calibrate(self._h, _ptr(q), _rptr(K), t_cur, _ptr(row), _ptr(ws), _stream()))

@@ -130,4 +130,10 @@ hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int n_w
 hipError_t launch_stream_copy(const void* src, size_t bytes, void* dst, int n_wg, hipStream_t st);
 hipError_t launch_push_row(const Shape& s, float* hist, int slot, const float* row, hipStream_t st);
 
+// Floats of workspace that launch_sparse_decode touches (the split partials, which lead the layout).
+size_t sparse_ws_floats(const Shape& s);
+// The current device's copy of the library's static scratch array (for callers that may not allocate) and its
+// size in bytes; looked up once per device.  Returns hipSuccess or the lookup error.
+hipError_t static_scratch(float** ptr, size_t* bytes);
+
 }  // namespace ap

@@ -32,6 +32,9 @@ WsLayout ws_layout(const Shape& s) {
   return w;
 }
 
+// The split partials lead the layout; a context with one workgroup per instance has none.
+size_t sparse_ws_floats(const Shape& s) { return s.n_split > 1 ? ws_layout(s).cal_ml : 0; }
+
 static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // Workgroups per instance for sparse decode: enough to give the chip work when there are few
@@ -394,6 +397,25 @@ int ap_sparse_decode(ap_ctx* ctx, const void* q, const void* K, const void* V, i
   return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+int ap_sparse_decode_noalloc(ap_ctx* ctx, const void* q, const void* K, const void* V, int32_t t_cur,
+                             const int32_t* idx, const int32_t* cnt, float* out, float* row, void* stream) {
+  if (ctx == nullptr) return AP_ERR_ARG;
+  AP_REQUIRE_PTR(q); AP_REQUIRE_PTR(K); AP_REQUIRE_PTR(V); AP_REQUIRE_PTR(idx); AP_REQUIRE_PTR(cnt);
+  AP_REQUIRE_PTR(out); AP_REQUIRE_PTR(row);
+  const Shape& s = ctx->s;
+  if (t_cur < 1 || t_cur > s.t_cap) return AP_ERR_RANGE;
+  if (ap::sparse_ws_floats(s) * sizeof(float) > AP_NOALLOC_SCRATCH_BYTES) return AP_ERR_RANGE;
+  float* ws = nullptr;
+  size_t bytes = 0;
+  if (ap::static_scratch(&ws, &bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return AP_ERR_HIP;
+  }
+  hipError_t e = ap::launch_sparse_decode(s, 0, s.n_inst, q, K, V, t_cur, idx, cnt, out, row, (size_t)s.nb_cap, ws,
+                                          static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 // A pointer a kernel may read: device memory, or host memory that is pinned and mapped.  Pageable host memory
 // would fault the GPU, so it is refused here.  The runtime is asked on every call: an answer remembered from an
 // earlier call could outlive the buffer it was given for.
@@ -601,7 +623,8 @@ const char* ap_strerror(int code) {
     case AP_OK: return "ok";
     case AP_ERR_ARG: return "invalid argument (null pointer, bad size or inconsistent configuration)";
     case AP_ERR_ALIGN: return "device pointer is not 16-byte aligned";
-    case AP_ERR_RANGE: return "t_cur, nb_cur or n_pushed outside the range the context was created for";
+    case AP_ERR_RANGE: return "t_cur, nb_cur or n_pushed outside the range the context was created for, or a "
+                              "context too large for the static scratch of a no-allocation call";
     case AP_ERR_HIP: return "a HIP runtime call failed";
     case AP_ERR_UNSUPPORTED: return "shape outside the compiled kernel set";
     case AP_ERR_STATE: return "predictor weights have not been set";

@@ -1,6 +1,13 @@
 // Kernels around attention_body.h: block-sparse decode (+ combine of splits) and dense calibration.
+#include <mutex>
+
 #include "attention_body.h"
 
+// Scratch for the entry point that must not allocate (ap_sparse_decode_noalloc): the split partials of one
+// sparse-decode call.  Every device the library runs on holds its own copy until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels get the address that call returned.
+constexpr size_t kStaticScratchBytes = AP_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace ap {
 namespace {
@@ -252,6 +259,27 @@ hipError_t launch_sparse_decode(const Shape& s, int inst0, int ninst, const void
   a.piece_blocks = s.k;
   a.table = s.table; a.n_phys = s.n_phys;
   AP_DISPATCH(run_sparse, s, ninst, a, st)
+}
+
+hipError_t static_scratch(float** ptr, size_t* bytes) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (addr[dev] == nullptr) {                            // once per device, with that device current
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = static_cast<float*>(addr[dev]);
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
 }
 
 hipError_t launch_calibrate(const Shape& s, const void* q, const void* K, int t_cur, float* row, float* ws,
