@@ -56,7 +56,8 @@ extern "C" {
 /* ap_config.flags */
 #define AP_FLAG_PREDICTOR_FP32 1 /* evaluate the incremental predictor with fp32 FMAs.  Default for 8/8
                                     and 16/32 channels: both conv layers on MFMA with f16 operands
-                                    and fp32 accumulation (pred moves by ~1e-4 of its magnitude).   */
+                                    and fp32 accumulation, on differences from the response to an
+                                    all-zero history (the scores move by ~1e-4 of their variable part). */
 
 /* Predictor evaluation modes (ap_predict_incremental, ap_step). */
 #define AP_PRED_REBASE 0  /* evaluate the full H x nb tile; (re)writes pstate if one is given        */
@@ -113,11 +114,15 @@ int ap_set_weights(ap_ctx* ctx, const float* host_blob, size_t n_floats, void* s
  * indices stay in logical block numbers.  block_table = NULL returns to the contiguous layout. */
 int ap_set_block_table(ap_ctx* ctx, const int32_t* block_table, int32_t n_phys_blocks);
 
-/* Algorithm 1 step 4: pred = F(A_H) on the H x nb_cur tile (zero outside it at every conv layer),
- * time average over H, raw linear head.
+/* Algorithm 1 step 4: the predictor F(A_H) on the H x nb_cur tile (zero outside it at every conv layer),
+ * time average over H, raw linear head.  The scores are only ever ranked (Algorithm 1 step 5), and most of F is a
+ * constant every block shares: P0, what the network answers to an all-zero history.  pred holds F - P0, so that
+ * fp32 resolves the part in which blocks differ; ap_score_offset returns P0 (float64, known once the weights are
+ * set; its border effects are those of a tile that is more than two blocks wide) for callers that want F itself.
  *   hist      device float [n_inst][R][nb_cap]
  *   n_pushed  rows pushed so far; the newest row is in slot (n_pushed - 1) % R
  *   pred      device float [n_inst][nb_cap]; entries [0, nb_cur) are written */
+double ap_score_offset(const ap_ctx* ctx);
 int ap_predict(ap_ctx* ctx, const float* hist, int64_t n_pushed, int32_t nb_cur, float* pred,
                void* ws, void* stream);
 

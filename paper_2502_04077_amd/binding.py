@@ -21,7 +21,7 @@ AP_FLAG_PREDICTOR_FP32 = 1
 AP_OK, AP_ERR_ARG, AP_ERR_ALIGN, AP_ERR_RANGE, AP_ERR_HIP, AP_ERR_UNSUPPORTED, AP_ERR_STATE = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_set_block_table",
+    "ap_create", "ap_destroy", "ap_workspace_bytes", "ap_hist_slots", "ap_nb_cap", "ap_set_weights", "ap_score_offset", "ap_set_block_table",
     "ap_predict", "ap_predict_incremental", "ap_select_topk", "ap_refresh_selection", "ap_sparse_decode", "ap_sparse_decode_noalloc", "ap_calibrate", "ap_update_history", "ap_step",
     "ap_prefetch_state_bytes", "ap_prefetch_blocks", "ap_append_kv", "ap_offload_begin", "ap_offload_step", "ap_stream_read", "ap_stream_copy", "ap_strerror",
 ]
@@ -62,6 +62,8 @@ def load_library() -> C.CDLL:
     lib.ap_nb_cap.argtypes = [vp]
     lib.ap_nb_cap.restype = i32
     lib.ap_set_weights.argtypes = [vp, vp, sz, vp]
+    lib.ap_score_offset.argtypes = [vp]
+    lib.ap_score_offset.restype = C.c_double
     lib.ap_set_block_table.argtypes = [vp, vp, i32]
     lib.ap_predict.argtypes = [vp, vp, i64, i32, vp, vp, vp]
     lib.ap_predict_incremental.argtypes = [vp, vp, i64, i32, i32, i32, vp, vp, vp, vp]
@@ -84,7 +86,8 @@ def load_library() -> C.CDLL:
     lib.ap_strerror.argtypes = [C.c_int]
     lib.ap_strerror.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("ap_workspace_bytes", "ap_prefetch_state_bytes", "ap_hist_slots", "ap_nb_cap", "ap_strerror"):
+        if name not in ("ap_workspace_bytes", "ap_prefetch_state_bytes", "ap_hist_slots", "ap_nb_cap", "ap_strerror",
+                        "ap_score_offset"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -160,6 +163,10 @@ class Context:
     def set_weights(self, blob: np.ndarray) -> None:
         blob = np.ascontiguousarray(blob, dtype=np.float32)
         _check(self._lib.ap_set_weights(self._h, blob.ctypes.data, blob.size, _stream()))
+
+    def score_offset(self) -> float:
+        """P0: pred holds the predictor's output minus this constant (see ap_predict in attnpred.h)."""
+        return float(self._lib.ap_score_offset(self._h))
 
     def set_block_table(self, table, n_phys_blocks: int = 0) -> None:
         """table: device int32 [n_inst][nb_cap] (kept alive by the caller), or None for the contiguous layout."""

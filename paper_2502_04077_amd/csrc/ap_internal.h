@@ -42,6 +42,23 @@ struct Shape {
   int n_phys;            // physical blocks in the pool
 };
 
+// Difference form of the predictor.  With an all-zero history the first layer gives c[ci] = relu(b1[ci]) at every
+// pixel of the tile and the second layer a constant per channel and row type (which of the three kernel rows fall
+// into the window).  Every kernel carries only the difference from that response - d1 = y1 - c (and -c where
+// layer 2 is padded with y1 = 0 beside the tile), d2 = relu(y2) - relu(B2) - so that fp32 sums and f16 operands
+// resolve the part of pred that differs between blocks instead of the constant all blocks share, and adds the
+// constant part P0 = b3 + (1/H) sum_r sum_c w3[c] relu(B2[type(r)][c]) is never added on the device: pred is
+// the score relative to P0 (fp32 would spend its mantissa on it), and ap_score_offset hands P0 to whoever wants
+// the raw head output.  The constants are worked out in float64 by ap_set_weights and appended to the weight
+// buffer at delta_const_offset floats:
+//   init1[c1] = min(b1, 0) | lo1[c1] = -max(b1, 0) |
+//   init2[type 4][c2] = min(B2, 0) | lo2[type 4][c2] = -max(B2, 0),   B2[type][co] = b2 + sum over the type's taps of w2 c
+// so that d1 = max(init1 + sum w1 x, lo1) and d2 = max(init2 + sum w2 d1, lo2) are one clamp each.
+// The interior state of the incremental form is the sum of the head-weighted d2 over rows 2..H-3 (type kRowAll).
+constexpr int kRowAll = 0, kRowTop = 1, kRowBot = 2, kRowOnly = 3;   // = (row == 0) + 2 * (row == H-1)
+__host__ __device__ constexpr int delta_const_offset(int c1, int c2);
+__host__ __device__ constexpr int delta_const_floats(int c1, int c2) { return 2 * c1 + 8 * c2; }
+
 // Workspace carve-up (float offsets from ws).
 struct WsLayout {
   size_t part_ml;     // [n_inst][n_split][g][2]        split max / sum
@@ -87,6 +104,12 @@ constexpr int kMfma16PairQ[8] = {0, 1, 1, 1, 2, 2, 3, 3};
 constexpr int kMfma16PairO[8] = {0, 0, 1, 2, 0, 2, 1, 2};
 // Kernel numbering -> the numbering predictor_tap uses (rows and outputs 1, 2 swap in the bottom half).
 __host__ __device__ constexpr int mfma16_phys(int half, int i) { return (half == 1 && (i == 1 || i == 2)) ? 3 - i : i; }
+
+__host__ __device__ constexpr int delta_const_offset(int c1, int c2) {
+  return (c1 == 8 && c2 == 8)     ? kMfmaTableFloatOffset + (kMfmaTableHalfs + kMfmaInteriorTableHalfs) / 2
+         : (c1 == 16 && c2 == 32) ? kMfma16TableFloatOffset + (kMfma16TableHalfs + kMfma16InteriorTableHalfs) / 2
+                                  : (10 * c1 + 9 * c1 * c2 + 2 * c2 + 1 + 3) / 4 * 4;
+}
 
 // Launchers.  Each returns hipSuccess or the launch error.
 // Full-tile predictor over columns [col_begin, nb_cur); also writes the interior state if pstate != null.

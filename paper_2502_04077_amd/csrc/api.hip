@@ -8,6 +8,7 @@ struct ap_ctx {
   ap::Shape s;
   float* dweights;      // device copy of the re-packed predictor weights, owned
   bool have_weights;
+  double score_offset;  // P0: what the predictor answers to an all-zero history (pred is relative to it)
   // ap_offload_*: "selection for the next token is written" / "its blocks are staged"; created on first use, owned
   hipEvent_t ev_selected, ev_staged;
   bool have_events;
@@ -106,6 +107,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
   s.n_phys = 0;
   ctx->dweights = nullptr;
   ctx->have_weights = false;
+  ctx->score_offset = 0.0;
   ctx->have_events = false;
   *out = ctx;
   return AP_OK;
@@ -157,9 +159,8 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   const float* w3 = b2 + c2;
   const float* b3 = w3 + c2;
   const bool mfma_table = (c1 == 8 && c2 == 8), mfma16_table = (c1 == 16 && c2 == 32);
-  const size_t total = mfma_table ? ap::kMfmaTableFloatOffset + (ap::kMfmaTableHalfs + ap::kMfmaInteriorTableHalfs) / 2
-                     : mfma16_table ? ap::kMfma16TableFloatOffset + (ap::kMfma16TableHalfs + ap::kMfma16InteriorTableHalfs) / 2
-                     : expect;
+  const size_t dc_off = ap::delta_const_offset(c1, c2);
+  const size_t total = dc_off + ap::delta_const_floats(c1, c2);
   std::vector<float> packed(total, 0.f);
   float* p = packed.data();
   for (int t = 0; t < 9; ++t)
@@ -291,6 +292,36 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
         t1[lane * 8 + e] = (_Float16)v;
       }
   }
+  double score_offset = 0.0;
+  {
+    // Constants of the difference form (layout: ap_internal.h), in float64.
+    const int H = ctx->s.H;
+    float* dc = packed.data() + dc_off;
+    std::vector<double> c(c1);
+    for (int ci = 0; ci < c1; ++ci) {
+      c[ci] = b1[ci] > 0.f ? (double)b1[ci] : 0.0;
+      dc[ci] = b1[ci] < 0.f ? b1[ci] : 0.f;
+      dc[c1 + ci] = (float)-c[ci];
+    }
+    double hc[4];
+    for (int type = 0; type < 4; ++type) {
+      // kernel rows inside the window: all three, not the first (row 0), not the last (row H-1), the middle one only
+      const int kh0 = (type & 1) ? 1 : 0, kh1 = (type & 2) ? 1 : 2;
+      hc[type] = 0.0;
+      for (int co = 0; co < c2; ++co) {
+        double B = b2[co];
+        for (int ci = 0; ci < c1; ++ci)
+          for (int kh = kh0; kh <= kh1; ++kh)
+            for (int kw = 0; kw < 3; ++kw) B += (double)w2[(((size_t)co * c1 + ci) * 3 + kh) * 3 + kw] * c[ci];
+        dc[2 * c1 + type * c2 + co] = (float)(B < 0.0 ? B : 0.0);
+        dc[2 * c1 + (4 + type) * c2 + co] = (float)(B > 0.0 ? -B : 0.0);
+        hc[type] += (double)w3[co] * (B > 0.0 ? B : 0.0);
+      }
+    }
+    double sum = 0.0;
+    for (int r = 0; r < H; ++r) sum += hc[(r == 0 ? 1 : 0) + (r == H - 1 ? 2 : 0)];
+    score_offset = (double)b3[0] + sum / H;
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (ctx->dweights == nullptr &&
       hipMalloc(reinterpret_cast<void**>(&ctx->dweights), total * sizeof(float)) != hipSuccess) {
@@ -301,8 +332,11 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
     return AP_ERR_HIP;
   if (hipStreamSynchronize(st) != hipSuccess) return AP_ERR_HIP;   // `packed` dies on return
   ctx->have_weights = true;
+  ctx->score_offset = score_offset;
   return AP_OK;
 }
+
+double ap_score_offset(const ap_ctx* ctx) { return (ctx != nullptr && ctx->have_weights) ? ctx->score_offset : 0.0; }
 
 static int newest_slot_of(const Shape& s, int64_t n_pushed) {
   return n_pushed <= 0 ? s.R - 1 : (int)((n_pushed - 1) % s.R);

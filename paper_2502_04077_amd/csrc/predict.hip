@@ -2,9 +2,11 @@
 //   y1 = relu(conv3x3(x; w1) + b1)      1  -> C1 channels, zero padding 1 on both axes
 //   y2 = relu(conv3x3(y1; w2) + b2)     C1 -> C2 channels, zero padding 1 on both axes
 //   z  = mean over the H time rows of y2
-//   pred = b3 + sum_c w3[c] * z[c]
+//   F  = b3 + sum_c w3[c] * z[c]
 // evaluated on the H x nb_cur history tile of every instance (axis 0 of the 3x3 kernels is time,
 // axis 1 is the block axis; cross-correlation; padding is relative to the current tile at each layer).
+// All kernels work in the difference form described in ap_internal.h and write pred = F - P0, the score relative
+// to the network's response P0 to an all-zero history, which every block shares (the selection only ranks).
 //
 // Two kernels compute it.
 //
@@ -18,7 +20,7 @@
 // commute with a time shift away from the zero-padded first/last rows.  y2 row r depends on x rows
 // r-2..r+2, so rows 2..H-3 ("interior") of one step are rows 1..H-4 of the next.  Because the head is
 // linear, one float per column carries everything the interior contributes:
-//   state[j] = sum_{r=2}^{H-3} sum_c w3[c] * y2[c][r][j]
+//   state[j] = sum_{r=2}^{H-3} sum_c w3[c] * (y2[c][r][j] - its value for an all-zero history)
 // and one step is  state += (row entering the interior) - (row leaving it), plus a fresh evaluation
 // of the four border rows 0, 1, H-2, H-1.  That is 6 y2 rows and 8 y1 rows per column instead of H,
 // from 10 history rows instead of H; the ring's spare slot still holds the row that left the window,
@@ -67,19 +69,20 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
     for (int e = tid; e < kYR * kYW; e += kPredThreads) {
       const int yr = e / kYW, yc = e - yr * kYW;
       const int r = r0 - 1 + yr, j = c0 - 1 + yc;
-      const bool inside = r >= 0 && r < H && j >= 0 && j < nb_cur;
       float x[3][3];
 #pragma unroll
       for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) x[kh][kw] = s_x[(yr + kh) * kXW + yc + kw];
-      y1_pixel<C1, C2>(W, x, inside, s_y1 + yr * kYW + yc, kYR * kYW);
+      y1_pixel<C1, C2>(W, x, r >= 0 && r < H, j >= 0 && j < nb_cur, s_y1 + yr * kYW + yc, kYR * kYW);
     }
     __syncthreads();
     // 3. y2 for rows r0+2rg, r0+2rg+1 of column c0+col, all C2 channels.
+    const int ra = r0 + 2 * rg;               // (the same for the whole wave: scalar loads of the constants)
+    const int ty0 = __builtin_amdgcn_readfirstlane(row_type(ra, H)), ty1 = __builtin_amdgcn_readfirstlane(row_type(ra + 1, H));
     float acc0[C2], acc1[C2];
 #pragma unroll
-    for (int c = 0; c < C2; ++c) { acc0[c] = W.b2[c]; acc1[c] = acc0[c]; }
+    for (int c = 0; c < C2; ++c) { acc0[c] = W.init2[ty0 * C2 + c]; acc1[c] = W.init2[ty1 * C2 + c]; }
 #pragma unroll 1
     for (int ci = 0; ci < C1; ++ci) {
       const float* yb = s_y1 + (ci * kYR + 2 * rg) * kYW + col;
@@ -100,12 +103,11 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
         }
       }
     }
-    const int ra = r0 + 2 * rg;
     float h0 = 0.f, h1 = 0.f;
 #pragma unroll
     for (int c = 0; c < C2; ++c) {
-      h0 = fmaf(W.w3[c], fmaxf(acc0[c], 0.f), h0);
-      h1 = fmaf(W.w3[c], fmaxf(acc1[c], 0.f), h1);
+      h0 = fmaf(W.w3[c], fmaxf(acc0[c], W.lo2[ty0 * C2 + c]), h0);
+      h1 = fmaf(W.w3[c], fmaxf(acc1[c], W.lo2[ty1 * C2 + c]), h1);
     }
     if (ra < H) { if (ra >= 2 && ra <= H - 3) w_int += h0; else w_bor += h0; }
     if (ra + 1 < H) { if (ra + 1 >= 2 && ra + 1 <= H - 3) w_int += h1; else w_bor += h1; }
@@ -121,7 +123,7 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
     const float sb = (s_z[1 * kTW + tid] + s_z[3 * kTW + tid]) + (s_z[5 * kTW + tid] + s_z[7 * kTW + tid]);
     const size_t o = (size_t)inst * nb_cap + c0 + tid;
     if (pstate != nullptr) pstate[o] = si;
-    pred[o] = W.b3[0] + (si + sb) / (float)H;
+    pred[o] = (si + sb) / (float)H;
   }
 }
 
@@ -151,7 +153,7 @@ __device__ __forceinline__ void y2_valu(const Weights<C1, C2>& W, const float* y
 #pragma unroll
   for (int k = 0; k < 3; ++k)
 #pragma unroll
-    for (int c = 0; c < C2; ++c) o[k][c] = W.b2[c];
+    for (int c = 0; c < C2; ++c) o[k][c] = W.init2[inc_row_type(HF, k) * C2 + c];
 #pragma unroll 1
   for (int ci = 0; ci < C1; ++ci) {
     const_f32_ptr wc = W.w2r + ci * 9 * C2;
@@ -193,14 +195,14 @@ __device__ __forceinline__ void stage_x_rows(float* s_x, const float* hist_inst,
 
 // Writes state and pred for column c0 + tid from the four head-weighted partial sums in s_red[2][2][LD].
 template <int LD>
-__device__ __forceinline__ void finish_column(const float* s_red, int tid, size_t o, int advance, float b3, int H,
-                                     float* pstate, float* pred) {
+__device__ __forceinline__ void finish_column(const float* s_red, int tid, size_t o, int advance, int H, float* pstate,
+                                     float* pred) {
   float st = pstate[o];
   if (advance) {
     st = (st - s_red[0 * LD + tid]) + s_red[2 * LD + tid];
     pstate[o] = st;
   }
-  pred[o] = b3 + (st + (s_red[1 * LD + tid] + s_red[3 * LD + tid])) / (float)H;
+  pred[o] = (st + (s_red[1 * LD + tid] + s_red[3 * LD + tid])) / (float)H;
 }
 
 template <int C1, int C2, int IW>
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
     for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
       for (int kw = 0; kw < 3; ++kw) x[kh][kw] = (kh == zero_kh) ? 0.f : xs[(base + kh) * XW + yc + kw];
-    y1_pixel<C1, C2>(W, x, j >= 0 && j < nb_cur, s_y1 + ((hf * 4 + q) * C1) * YW + yc, YW);
+    y1_pixel<C1, C2>(W, x, true, j >= 0 && j < nb_cur, s_y1 + ((hf * 4 + q) * C1) * YW + yc, YW);
   };
   {
     const int hf = tid / IW, yc = tid - hf * IW;
@@ -251,16 +253,16 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
     float moving = 0.f, b1sum = 0.f, b2sum = 0.f;   // head-weighted: the moving row, the two border rows
 #pragma unroll
     for (int c = 0; c < C2; ++c) {
-      moving = fmaf(W.w3[c], fmaxf(o[0][c], 0.f), moving);
-      b1sum = fmaf(W.w3[c], fmaxf(o[1][c], 0.f), b1sum);
-      b2sum = fmaf(W.w3[c], fmaxf(o[2][c], 0.f), b2sum);
+      moving = fmaf(W.w3[c], fmaxf(o[0][c], W.lo2[kRowAll * C2 + c]), moving);
+      b1sum = fmaf(W.w3[c], fmaxf(o[1][c], W.lo2[(hf == 0 ? kRowTop : kRowAll) * C2 + c]), b1sum);
+      b2sum = fmaf(W.w3[c], fmaxf(o[2][c], W.lo2[(hf == 0 ? kRowAll : kRowBot) * C2 + c]), b2sum);
     }
     s_red[(hf * 2 + 0) * IW + col] = moving;
     s_red[(hf * 2 + 1) * IW + col] = b1sum + b2sum;
   }
   __syncthreads();
   if (tid < IW && c0 + tid < nb_cur)
-    finish_column<IW>(s_red, tid, (size_t)inst * nb_cap + c0 + tid, advance, W.b3[0], H, pstate, pred);
+    finish_column<IW>(s_red, tid, (size_t)inst * nb_cap + c0 + tid, advance, H, pstate, pred);
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4)))   // four workgroups per CU: 128 VGPRs
@@ -338,32 +340,34 @@ __global__ __launch_bounds__(kWave) void predict_columns_kernel(const float* __r
     for (int dr = 0; dr < 5; ++dr)
 #pragma unroll
       for (int dc = 0; dc < 5; ++dc) x[dr][dc] = s_x[(r + dr) * 5 + dc];
+    const float* init2 = wts_global + delta_const_offset(C1, C2) + 2 * C1 + row_type(r, H) * C2;   // (per lane)
     float acc[C2];
 #pragma unroll
-    for (int c = 0; c < C2; ++c) acc[c] = W.b2[c];
+    for (int c = 0; c < C2; ++c) acc[c] = init2[c];
 #pragma unroll 1
     for (int ci = 0; ci < C1; ++ci) {
       const_f32_ptr wc = W.w2r + ci * 9 * C2;
+      const float lo = W.lo1[ci];
 #pragma unroll
       for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
         for (int kw = 0; kw < 3; ++kw) {
-          // y1[ci] at (r + kh - 1, j + kw - 1): zero outside the tile
+          // d1[ci] at (r + kh - 1, j + kw - 1): lo1 beside the tile, left out above and below the window
           const int rr = r + kh - 1, jj = j + kw - 1;
-          float a = W.b1[ci];
+          float a = W.init1[ci];
 #pragma unroll
           for (int a_kh = 0; a_kh < 3; ++a_kh)
 #pragma unroll
             for (int a_kw = 0; a_kw < 3; ++a_kw)
               a = fmaf(W.w1r[(a_kh * 3 + a_kw) * C1 + ci], x[kh + a_kh][kw + a_kw], a);
-          const float y = (rr >= 0 && rr < H && jj >= 0 && jj < nb_cur) ? fmaxf(a, 0.f) : 0.f;
+          const float y = (rr >= 0 && rr < H) ? ((jj >= 0 && jj < nb_cur) ? fmaxf(a, lo) : lo) : 0.f;
 #pragma unroll
           for (int c = 0; c < C2; ++c) acc[c] = fmaf(wc[(kh * 3 + kw) * C2 + c], y, acc[c]);
         }
     }
     float hsum = 0.f;
 #pragma unroll
-    for (int c = 0; c < C2; ++c) hsum = fmaf(W.w3[c], fmaxf(acc[c], 0.f), hsum);
+    for (int c = 0; c < C2; ++c) hsum = fmaf(W.w3[c], fmaxf(acc[c], init2[4 * C2 + c]), hsum);
     if (r >= 2 && r <= H - 3) w_int += hsum; else w_bor += hsum;
   }
 #pragma unroll
@@ -374,7 +378,7 @@ __global__ __launch_bounds__(kWave) void predict_columns_kernel(const float* __r
   if (lane == 0) {
     const size_t o = (size_t)inst * nb_cap + j;
     if (pstate != nullptr) pstate[o] = w_int;
-    pred[o] = W.b3[0] + (w_int + w_bor) / (float)H;
+    pred[o] = (w_int + w_bor) / (float)H;
   }
 }
 

@@ -22,35 +22,44 @@ __device__ __forceinline__ const_f32_ptr as_constant(const float* p) {
 }
 
 template <int C1, int C2> struct Weights {
-  const_f32_ptr w1r, b1, w2r, b2, w3, b3;
+  const_f32_ptr w1r, w2r, w3;
+  const_f32_ptr init1, lo1, init2, lo2;       // constants of the difference form (ap_internal.h)
   __device__ explicit Weights(const float* g) {
     const_f32_ptr W = as_constant(g);
     w1r = W;                              // [kh][kw][C1]
-    b1 = W + 9 * C1;
     w2r = W + 10 * C1;                    // [ci][kh][kw][C2]
-    b2 = w2r + 9 * C1 * C2;
-    w3 = b2 + C2;
-    b3 = w3 + C2;
+    w3 = w2r + 9 * C1 * C2 + C2;
+    init1 = W + delta_const_offset(C1, C2);
+    lo1 = init1 + C1;
+    init2 = lo1 + C1;                     // [type][C2]
+    lo2 = init2 + 4 * C2;                 // [type][C2]
   }
 };
+
+// Row type of history row r (which kernel rows of the second layer fall inside the window).
+__device__ __forceinline__ int row_type(int r, int H) { return (r == 0 ? 1 : 0) + (r == H - 1 ? 2 : 0); }
 
 __device__ __forceinline__ int ring_slot(int newest_slot, int H, int R, int r) {
   int slot = (newest_slot - (H - 1 - r)) % R;   // logical row r (H-1 = newest, -1 = the row that just left)
   return slot < 0 ? slot + R : slot;
 }
 
-// One y1 pixel, all C1 channels, from a 3x3 x neighbourhood.
+// One first-layer pixel, all C1 channels, from a 3x3 x neighbourhood, as the difference d1 = y1 - relu(b1).
+// A pixel beside the tile in its own row stands for y1 = 0 (layer-2 padding), i.e. d1 = -relu(b1) = lo1; a pixel
+// of a row outside the window is left out of the second layer's sums altogether (its constant is not part of
+// that row type's B2), i.e. 0.
 template <int C1, int C2>
-__device__ __forceinline__ void y1_pixel(const Weights<C1, C2>& W, const float (&x)[3][3], bool inside, float* dst,
-                                int chan_stride) {
+__device__ __forceinline__ void y1_pixel(const Weights<C1, C2>& W, const float (&x)[3][3], bool row_inside,
+                                bool col_inside, float* dst, int chan_stride) {
 #pragma unroll
   for (int c = 0; c < C1; ++c) {
-    float a = W.b1[c];
+    float a = W.init1[c];
 #pragma unroll
     for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
       for (int kw = 0; kw < 3; ++kw) a = fmaf(W.w1r[(kh * 3 + kw) * C1 + c], x[kh][kw], a);
-    dst[c * chan_stride] = inside ? fmaxf(a, 0.f) : 0.f;
+    const float lo = W.lo1[c];
+    dst[c * chan_stride] = row_inside ? (col_inside ? fmaxf(a, lo) : lo) : 0.f;
   }
 }
 
@@ -58,6 +67,12 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+// Row type of output k of a half of the incremental kernels (0 = top: leaving row, row 0, row 1; 1 = bottom:
+// entering row, row H-2, row H-1): the moving row and rows 1, H-2 meet all three kernel rows, rows 0 and H-1 two.
+__host__ __device__ constexpr int inc_row_type(int half, int k) {
+  return half == 0 ? (k == 1 ? kRowTop : kRowAll) : (k == 2 ? kRowBot : kRowAll);
+}
 
 // One staged x value of the MFMA variants: 2^12 x as f16 hi (low half of the word) + f16 lo (high half);
 // hi + lo carry 22 significant bits, so tiny probabilities keep their precision.
@@ -132,16 +147,27 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
 #pragma unroll
   for (int s = 0; s < 6; ++s) A2[s] = tab2[s * kWave + lane];
   const half8 A1 = tab1[lane];
+  // Difference form (ap_internal.h): accumulators start at 2^8 init, the ReLU is a clamp at 2^8 lo.
+  const float* dc = wts_global + delta_const_offset(C, C);
   float16v b1acc, b2acc;                                 // entry v is D row 8 (v / 4) + c, c = 4 hsel + v % 4
-  float w3v[4];
+  float w3v[4], lo2v[12];
+  half4 lo1h;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    b1acc[v] = kAccScale * wts_global[9 * C + 4 * hsel + v % 4];
-    b2acc[v] = v < 12 ? kAccScale * wts_global[10 * C + 9 * C * C + 4 * hsel + v % 4] : 0.f;
+    b1acc[v] = kAccScale * dc[4 * hsel + v % 4];
+    b2acc[v] = v < 12 ? kAccScale * dc[2 * C + inc_row_type(0, v / 4) * C + 4 * hsel + v % 4] : 0.f;
+    if (hf && v < 12) b2acc[v] = kAccScale * dc[2 * C + inc_row_type(1, v / 4) * C + 4 * hsel + v % 4];
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) w3v[j] = wts_global[10 * C + 9 * C * C + C + 4 * hsel + j] * (1.f / kAccScale);
-  const float b3 = wts_global[10 * C + 9 * C * C + 2 * C];
+  for (int v = 0; v < 12; ++v) {
+    const int ty = hf ? inc_row_type(1, v / 4) : inc_row_type(0, v / 4);
+    lo2v[v] = kAccScale * dc[2 * C + (4 + ty) * C + 4 * hsel + v % 4];
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    w3v[j] = wts_global[10 * C + 9 * C * C + C + 4 * hsel + j] * (1.f / kAccScale);
+    lo1h[j] = (_Float16)(kAccScale * dc[C + 4 * hsel + j]);
+  }
   const float inv_H = 1.f / (float)H;                     // the time mean as a multiplication
   // layer-1 K slot e of this lane is (x row, kw) = divmod(8 hsel + e, 3); slot 15 has zero weights
   int xoff[8];
@@ -214,12 +240,12 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
         half4 h;
 #pragma unroll
         for (int c = 0; c < 4; ++c) h[c] = (_Float16)acc[4 * q + c];
-        h = __builtin_elementwise_max(h, (half4)(_Float16)0);
+        h = __builtin_elementwise_max(h, lo1h);
         reinterpret_cast<half4*>(s_y1 + (hf * 4 + q) * YW + yc)[hsel] = h;
       }
-      if (j < 0 || j >= nb_cur) {                        // layer-2 padding: y1 is zero outside the tile
+      if (j < 0 || j >= nb_cur) {                        // layer-2 padding: y1 = 0 beside the tile, d1 = lo1
 #pragma unroll
-        for (int q = 0; q < 4; ++q) reinterpret_cast<half4*>(s_y1 + (hf * 4 + q) * YW + yc)[hsel] = (half4)(_Float16)0;
+        for (int q = 0; q < 4; ++q) reinterpret_cast<half4*>(s_y1 + (hf * 4 + q) * YW + yc)[hsel] = lo1h;
       }
     }
     __syncthreads();
@@ -242,7 +268,7 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
       for (int k = 0; k < 3; ++k) {
         float t = 0.f;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) t = fmaf(w3v[jj], __builtin_amdgcn_fmed3f(acc[4 * k + jj], 0.f, inf), t);
+        for (int jj = 0; jj < 4; ++jj) t = fmaf(w3v[jj], __builtin_amdgcn_fmed3f(acc[4 * k + jj], lo2v[4 * k + jj], inf), t);
         p[k] = t;
       }
       s_red[((hf * 2 + 0) * 2 + hsel) * LD + cb + n] = p[0];
@@ -258,7 +284,7 @@ __device__ __forceinline__ void predict_inc_mfma_body(const float* __restrict__ 
         st = (st - part(0, 0)) + part(1, 0);
         pstate_inst[(unsigned)(c0 + tid)] = st;
       }
-      pred_inst[(unsigned)(c0 + tid)] = b3 + (st + (part(0, 1) + part(1, 1))) * inv_H;
+      pred_inst[(unsigned)(c0 + tid)] = (st + (part(0, 1) + part(1, 1))) * inv_H;
     }
     if (more) stash(tile + 1, s_xb + (((tile - t_begin) & 1) ^ 1) * XBUF);
     pst_cur = pst_next;

@@ -31,7 +31,8 @@ namespace {
 
 constexpr int kP16IW = kPmIW, kP16XW = kPmXW, kP16YW = kPmYW, kP16LD = kPmLD, kP16XBuf = kPmXBuf;   // same tile geometry
 constexpr int kP16Y1Floats = 2 * 4 * 2 * kP16YW * 4;
-constexpr int kP16ConstFloats = 2 * 2 * kWave * 4 + 2 * 16 + 2 * 16 + 2 * 8;   // A1 | 2^8 b1 | 2^-8 w3 | x offsets
+// A1 | 2^8 init1 | 2^-8 w3 | x offsets | 2^8 init2 of (half, row type all / border) | 2^8 lo2 of the same | 2^8 lo1 (f16)
+constexpr int kP16ConstFloats = 2 * 2 * kWave * 4 + 2 * 16 + 2 * 16 + 2 * 8 + 2 * 2 * 2 * 16 + 2 * 2 * 2 * 16 + 2 * 4;
 constexpr int kPred16LdsFloats = kP16Y1Floats + 2 * kP16XBuf + 8 * kP16LD + kP16ConstFloats;
 
 // Workgroup `chunk` of `n_chunks` of instance `inst` (256 threads); smem: kPred16LdsFloats floats, 16-byte aligned.
@@ -51,6 +52,11 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
   float* s_b1 = reinterpret_cast<float*>(s_a1 + 2 * 2 * kWave);   // [lane half 2][16] accumulator start of layer 1
   float* s_w3 = s_b1 + 2 * 16;                           // [lane half 2][16] head weight of accumulator entry v
   int* s_xoff = reinterpret_cast<int*>(s_w3 + 2 * 16);   // [lane half 2][8]  x offset of layer-1 K slot e
+  // Difference form (ap_internal.h): where the accumulators of the second layer start and where they are clamped,
+  // for the outputs that meet all three kernel rows (o0, o2) and for the half's border row (o1: row 0 or row H-1).
+  float* s_i2 = reinterpret_cast<float*>(s_xoff + 2 * 8);   // [half 2][all | border][lane half 2][16]
+  float* s_l2 = s_i2 + 2 * 2 * 2 * 16;                      // the same layout
+  half4* s_l1 = reinterpret_cast<half4*>(s_l2 + 2 * 2 * 2 * 16);   // [channel half pl 2][lane half 2] clamp of the first layer
 
   const int tiles = (nb_cur + IW - 1) / IW;
   const int per_wg = (tiles + n_chunks - 1) / n_chunks;
@@ -73,15 +79,26 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
 #pragma unroll
   for (int i = 0; i < 24; ++i) A2[i] = tab2[i * kWave + lane];
   const float* b2 = wts_global + 10 * C1 + 9 * C1 * C2;
-  const float b3 = b2[2 * C2];
-  float16v b2acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) b2acc[v] = kAccScale * b2[8 * (v / 4) + 4 * hsel + v % 4];   // D row of entry v
+  const float* dc = wts_global + delta_const_offset(C1, C2);
   s_a1[tid] = tab[2 * 24 * kWave + tid];
   if (tid < 32) {
-    const int h = tid >> 4, v = tid & 15, row = 8 * (v / 4) + 4 * h + v % 4;
-    s_b1[tid] = kAccScale * wts_global[9 * C1 + row % C1];
+    const int h = tid >> 4, v = tid & 15, row = 8 * (v / 4) + 4 * h + v % 4;   // D row of accumulator entry v
+    s_b1[tid] = kAccScale * dc[row % C1];
     s_w3[tid] = b2[C2 + row] * (1.f / kAccScale);
+  }
+  if (tid < 128) {
+    const int half = tid >> 6, border = (tid >> 5) & 1, h = (tid >> 4) & 1, v = tid & 15;
+    const int row = 8 * (v / 4) + 4 * h + v % 4;
+    const int type = border ? (half == 0 ? kRowTop : kRowBot) : kRowAll;
+    s_i2[tid] = kAccScale * dc[2 * C1 + type * C2 + row];
+    s_l2[tid] = kAccScale * dc[2 * C1 + (4 + type) * C2 + row];
+  }
+  if (tid < 4) {
+    const int pl = tid >> 1, h = tid & 1;
+    half4 l;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) l[c] = (_Float16)(kAccScale * dc[C1 + 8 * pl + 4 * h + c]);
+    s_l1[tid] = l;
   }
   if (tid < 16) {   // layer-1 K slot 8 h + e is (x row, kw) = divmod(8 h + e, 3); slot 15 has zero weights
     const int k = tid;
@@ -139,6 +156,7 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
       for (int v = 0; v < 16; ++v) b1acc[v] = s_b1[fresh + hsel * 16 + v];
 #pragma unroll
       for (int e = 0; e < 8; ++e) xoff[e] = s_xoff[fresh + hsel * 8 + e];
+      const half4 lo1a = s_l1[fresh + 0 * 2 + hsel], lo1b = s_l1[fresh + 1 * 2 + hsel];
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk) {
         const int yc = ((wave & 1) * 2 + blk) * 32 + n;  // y1 column 0..127  <->  tile column c0 - 1 + yc
@@ -164,22 +182,28 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
               half4 h;
 #pragma unroll
               for (int c = 0; c < 4; ++c) h[c] = (_Float16)acc[8 * ql + 4 * p + c];
-              h = __builtin_elementwise_max(h, (half4)(_Float16)0);
+              h = __builtin_elementwise_max(h, p ? lo1b : lo1a);
               reinterpret_cast<half4*>(s_y1 + ((hf * 4 + 2 * rb + ql) * 2 + p) * YW + yc)[hsel] = h;
             }
         }
-        if (outside) {                                   // layer-2 padding: y1 is zero outside the tile
+        if (outside) {                                   // layer-2 padding: y1 = 0 beside the tile, d1 = lo1
 #pragma unroll
           for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int p = 0; p < 2; ++p)
-              reinterpret_cast<half4*>(s_y1 + ((hf * 4 + q) * 2 + p) * YW + yc)[hsel] = (half4)(_Float16)0;
+              reinterpret_cast<half4*>(s_y1 + ((hf * 4 + q) * 2 + p) * YW + yc)[hsel] = p ? lo1b : lo1a;
         }
       }
     }
     __syncthreads();
 
     // Layer 2 and the head.
+    float16v b2acc, b2bor;                // accumulator starts: rows with all kernel rows (o0, o2), the border row (o1)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      b2acc[v] = s_i2[fresh + ((hf * 2 + 0) * 2 + hsel) * 16 + v];
+      b2bor[v] = s_i2[fresh + ((hf * 2 + 1) * 2 + hsel) * 16 + v];
+    }
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int cb = ((wave & 1) * 2 + blk) * 32;
@@ -194,7 +218,7 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
       for (int kw = 0; kw < 3; ++kw) {
         const half8 B = yq[1 * 2 * YW + kw];
         acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A2[1 * 3 + kw], B, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A2[2 * 3 + kw], B, kw == 0 ? b2acc : acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A2[2 * 3 + kw], B, kw == 0 ? b2bor : acc1, 0, 0, 0);
         acc2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A2[3 * 3 + kw], B, kw == 0 ? b2acc : acc2, 0, 0, 0);
       }
 #pragma unroll
@@ -213,9 +237,10 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const float w = s_w3[fresh + hsel * 16 + v];
-        t0 = fmaf(w, __builtin_amdgcn_fmed3f(acc0[v], 0.f, inf), t0);
-        t1 = fmaf(w, __builtin_amdgcn_fmed3f(acc1[v], 0.f, inf), t1);
-        t2 = fmaf(w, __builtin_amdgcn_fmed3f(acc2[v], 0.f, inf), t2);
+        const float la = s_l2[fresh + ((hf * 2 + 0) * 2 + hsel) * 16 + v], lb = s_l2[fresh + ((hf * 2 + 1) * 2 + hsel) * 16 + v];
+        t0 = fmaf(w, __builtin_amdgcn_fmed3f(acc0[v], la, inf), t0);
+        t1 = fmaf(w, __builtin_amdgcn_fmed3f(acc1[v], lb, inf), t1);
+        t2 = fmaf(w, __builtin_amdgcn_fmed3f(acc2[v], la, inf), t2);
       }
       s_red[((hf * 2 + 0) * 2 + hsel) * LD + cb + n] = t0;
       s_red[((hf * 2 + 1) * 2 + hsel) * LD + cb + n] = t1 + t2;
@@ -230,7 +255,7 @@ __device__ __forceinline__ void predict_inc_mfma16_body(const float* __restrict_
         st = (st - part(0, 0)) + part(1, 0);
         pstate_inst[c0 + tid] = st;
       }
-      pred_inst[c0 + tid] = b3 + (st + (part(0, 1) + part(1, 1))) / (float)H;
+      pred_inst[c0 + tid] = (st + (part(0, 1) + part(1, 1))) / (float)H;
     }
     if (more) stash(tile + 1, s_xb + (((tile - t_begin) & 1) ^ 1) * XBUF);
     pst_cur = pst_next;

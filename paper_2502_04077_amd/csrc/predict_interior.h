@@ -1,5 +1,5 @@
 // MFMA evaluation of the interior state of the incremental predictor from scratch (8/8 channels):
-//   state[j] = sum_{r=2}^{H-3} sum_c w3[c] * relu(y2[c][r][j])
+//   state[j] = sum_{r=2}^{H-3} sum_c w3[c] * (relu(y2[c][r][j]) - relu(B2[c]))      (difference form, ap_internal.h)
 // i.e. what a re-base needs; the border rows 0, 1, H-2, H-1 and the head are then added by the incremental
 // kernel run without an advance.  Same arithmetic as predict_inc_mfma_body (f16 operands, x as hi + lo of 2^12 x,
 // fp32 accumulation, y1 kept as f16 of 2^8 y1), so a re-based state continues the advanced one without a step.
@@ -54,15 +54,23 @@ __device__ __forceinline__ void predict_interior_mfma_body(const float* __restri
 #pragma unroll
   for (int s = 0; s < 8; ++s) A2[s] = tab[s * kWave + lane];
   const half8 A1 = tab[8 * kWave + lane];
+  // Difference form (ap_internal.h): accumulators start at 2^8 init, the ReLU is a clamp at 2^8 lo; every row
+  // here meets all three kernel rows.
+  const float* dc = wts_global + delta_const_offset(C, C);
   float16v b1acc, b2acc;                                 // entry v is D row 8 (v / 4) + c, c = 4 hsel + v % 4
-  float w3v[4];
+  float w3v[4], lo2v[4];
+  half4 lo1h;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    b1acc[v] = v < 12 ? kAccScale * wts_global[9 * C + 4 * hsel + v % 4] : 0.f;
-    b2acc[v] = v < 12 ? kAccScale * wts_global[10 * C + 9 * C * C + 4 * hsel + v % 4] : 0.f;
+    b1acc[v] = v < 12 ? kAccScale * dc[4 * hsel + v % 4] : 0.f;
+    b2acc[v] = v < 12 ? kAccScale * dc[2 * C + kRowAll * C + 4 * hsel + v % 4] : 0.f;
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) w3v[j] = wts_global[10 * C + 9 * C * C + C + 4 * hsel + j] * (1.f / kAccScale);
+  for (int j = 0; j < 4; ++j) {
+    w3v[j] = wts_global[10 * C + 9 * C * C + C + 4 * hsel + j] * (1.f / kAccScale);
+    lo2v[j] = kAccScale * dc[2 * C + (4 + kRowAll) * C + 4 * hsel + j];
+    lo1h[j] = (_Float16)(kAccScale * dc[C + 4 * hsel + j]);
+  }
   int xoff[8];                                           // layer-1 K slot e of this lane -> offset in s_x
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -135,8 +143,8 @@ __device__ __forceinline__ void predict_interior_mfma_body(const float* __restri
       half4 h;
 #pragma unroll
       for (int c = 0; c < 4; ++c) h[c] = (_Float16)acc[4 * q + c];
-      h = __builtin_elementwise_max(h, (half4)(_Float16)0);
-      if (y1_outside) h = (half4)(_Float16)0;            // layer-2 padding: y1 is zero outside the tile
+      h = __builtin_elementwise_max(h, lo1h);
+      if (y1_outside) h = lo1h;                          // layer-2 padding: y1 = 0 beside the tile, d1 = lo1
       reinterpret_cast<half4*>(dst + q * YW)[hsel] = h;
     }
     asm volatile("" ::: "memory");
@@ -167,7 +175,7 @@ __device__ __forceinline__ void predict_interior_mfma_body(const float* __restri
     for (int o = 0; o < 3; ++o) {
       float t = 0.f;
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) t = fmaf(w3v[jj], __builtin_amdgcn_fmed3f(acc[4 * o + jj], 0.f, inf), t);
+      for (int jj = 0; jj < 4; ++jj) t = fmaf(w3v[jj], __builtin_amdgcn_fmed3f(acc[4 * o + jj], lo2v[jj], inf), t);
       if (o < left) sum += t;
     }
   }
@@ -209,17 +217,25 @@ __device__ __forceinline__ void predict_interior_mfma16_body(const float* __rest
 #pragma unroll
   for (int i = 0; i < 9; ++i) A2[i] = tab[i * kWave + lane];
   const half8 A1 = tab[9 * kWave + lane];
-  const float* b1 = wts_global + 9 * C1;
+  // Difference form (ap_internal.h): accumulators start at 2^8 init, the ReLU is a clamp at 2^8 lo; every row
+  // here meets all three kernel rows.
+  const float* dc = wts_global + delta_const_offset(C1, C2);
   const float* b2 = wts_global + 10 * C1 + 9 * C1 * C2;
   float16v b1acc, b2acc;
-  float w3v[16];
+  float w3v[16], lo2v[16];
+  half4 lo1h[2];                                         // channels 8 pl + 4 hsel .. + 3
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int row = 8 * (v / 4) + 4 * hsel + v % 4;      // D row of accumulator entry v
-    b1acc[v] = kAccScale * b1[row % C1];
-    b2acc[v] = kAccScale * b2[row];
+    b1acc[v] = kAccScale * dc[row % C1];
+    b2acc[v] = kAccScale * dc[2 * C1 + kRowAll * C2 + row];
+    lo2v[v] = kAccScale * dc[2 * C1 + (4 + kRowAll) * C2 + row];
     w3v[v] = b2[C2 + row] * (1.f / kAccScale);
   }
+#pragma unroll
+  for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) lo1h[pl][c] = (_Float16)(kAccScale * dc[C1 + 8 * pl + 4 * hsel + c]);
   int xoff[8];                                           // layer-1 K slot e of this lane -> offset in s_x
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -292,8 +308,8 @@ __device__ __forceinline__ void predict_interior_mfma16_body(const float* __rest
           half4 h;
 #pragma unroll
           for (int c = 0; c < 4; ++c) h[c] = (_Float16)acc[8 * q + 4 * pl + c];
-          h = __builtin_elementwise_max(h, (half4)(_Float16)0);
-          if (y1_outside) h = (half4)(_Float16)0;        // layer-2 padding: y1 is zero outside the tile
+          h = __builtin_elementwise_max(h, lo1h[pl]);
+          if (y1_outside) h = lo1h[pl];                  // layer-2 padding: y1 = 0 beside the tile, d1 = lo1
           reinterpret_cast<half4*>(s_y1 + ((2 * (p & 1) + q) * 2 + pl) * YW + n)[hsel] = h;
         }
       asm volatile("" ::: "memory");
@@ -325,8 +341,8 @@ __device__ __forceinline__ void predict_interior_mfma16_body(const float* __rest
       float t0 = 0.f, t1 = 0.f;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        t0 = fmaf(w3v[v], __builtin_amdgcn_fmed3f(acc0[v], 0.f, inf), t0);
-        t1 = fmaf(w3v[v], __builtin_amdgcn_fmed3f(acc1[v], 0.f, inf), t1);
+        t0 = fmaf(w3v[v], __builtin_amdgcn_fmed3f(acc0[v], lo2v[v], inf), t0);
+        t1 = fmaf(w3v[v], __builtin_amdgcn_fmed3f(acc1[v], lo2v[v], inf), t1);
       }
       sum += t0;
       if (2 * s + 1 < n_rows) sum += t1;

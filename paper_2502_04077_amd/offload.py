@@ -169,6 +169,10 @@ class OffloadRun:
     def out(self):
         return torch.cat([L.out for L in self.layers])
 
+    def score_offset(self) -> float:
+        """The constant the scores are relative to (the same for every layer: one predictor serves them all)."""
+        return self.layers[0].ctx.score_offset()
+
     def staged_selection(self):
         """Scores and selection made for the NEXT step: pred [n_inst][nb_cap], idx [n_inst][k], cnt [n_inst]."""
         return (torch.cat([L.pred for L in self.layers]), torch.cat([L.idx for L in self.layers]),

@@ -77,7 +77,7 @@ def _free_run(w, blob, dev, name):
             rrec[s, i, 1] = orc.recovery_rate(A, orc.expand_blocks(ref.blocks, b, t))
             if first_div[i] is not None:
                 continue                                   # the trajectories have parted: nothing to hold them to
-            gp = g_pred[i, :nb].astype(np.float64)
+            gp = g_pred[i, :nb].astype(np.float64) + run.ctx.score_offset()   # pred is relative to that constant
             err_all = np.abs(gp - ref.pred).max()
             assert err_all <= 1e-3 * np.abs(ref.pred).max(), f"{name} step {s} inst {i}: pred off by {err_all:.3e}"
             worst["pred"] = max(worst["pred"], err_all / np.abs(ref.pred).max())

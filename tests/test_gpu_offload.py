@@ -157,6 +157,7 @@ def test_offload_lockstep_vs_oracle(single_calls):
         run.warmup_calibrate(queries(w, j - H, dev), w.t0 - H + 1 + j)
     run.start(w.t_at(0))
     stats = ScoreStats()
+    off = run.score_offset()
     for s in range(w.steps):
         t = w.t_at(s)
         nb = run.nb(t)
@@ -172,11 +173,11 @@ def test_offload_lockstep_vs_oracle(single_calls):
         for i in range(w.n_inst):
             qi = to_f64(q[i])
             ref_pred = orc.predict(before[i], nb, wts)
-            assert_close(pred[i, :nb], ref_pred, f"step {s} inst {i} pred")
+            assert_close(pred[i, :nb].astype(np.float64) + off, ref_pred, f"step {s} inst {i} pred")
             got_idx = idx[i, :cnt[i]]
             exp_idx = orc.select_blocks(pred[i, :nb].astype(np.float64), nb, w.k_blocks, w.n_sink, w.n_local)
             assert got_idx.tolist() == exp_idx.tolist(), f"step {s} inst {i}: selection differs"
-            stats.add(f"step {s} inst {i}", pred[i, :nb].astype(np.float64), ref_pred, got_idx, nb, w.k_blocks,
+            stats.add(f"step {s} inst {i}", pred[i, :nb].astype(np.float64) + off, ref_pred, got_idx, nb, w.k_blocks,
                       w.n_sink, w.n_local)
             ref_out, A = orc.sparse_attention(qi, Kc[i], Vc[i], got_idx, b, t)
             for h in range(w.g):

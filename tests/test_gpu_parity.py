@@ -180,7 +180,8 @@ def test_predict_vs_oracle(H, nb, c1, c2, pushed):
     ws = torch.zeros((max(16, ctx.workspace_bytes()),), dtype=torch.uint8, device=dev)
     ctx.predict(hist, pushed, nb, pred, ws)
     torch.cuda.synchronize()
-    got = pred.cpu().numpy()
+    got = pred.cpu().numpy().astype(np.float64)
+    got[:, :nb] += ctx.score_offset()                   # pred is relative to the all-zero-history score
     for i in range(n_inst):
         logical = np.zeros((H, nb_cap))
         for r in range(H):
@@ -190,6 +191,42 @@ def test_predict_vs_oracle(H, nb, c1, c2, pushed):
         ref = orc.predict(logical, nb, wts)
         assert_close(got[i, :nb], ref, f"pred inst {i}")
         assert np.all(got[i, nb:] == -5.0)
+
+
+@pytest.mark.parametrize("H,c1,c2,fp32", [(64, 8, 8, 0), (64, 8, 8, 1), (16, 4, 4, 0), (64, 16, 32, 0), (6, 8, 8, 0),
+                                          (5, 8, 8, 0), (1, 4, 4, 0), (2, 8, 8, 0)])
+def test_score_offset_is_the_zero_history_score(H, c1, c2, fp32):
+    """pred is the predictor's output minus what it answers to an all-zero history (ap_score_offset).  So the offset
+    must equal the oracle's score of an all-zero tile away from the tile's edges, the kernels must return exact zeros
+    there for such a tile, and at the edge blocks (where the second layer's zero padding shows) offset + pred must
+    still be the oracle's score."""
+    dev = _dev()
+    ap = _ap()
+    n_inst, b, nb = 2, 16, 40
+    ctx = ap.Context(n_inst=n_inst, g=1, head_dim=64, block=b, hist_len=H, t_cap=(nb + 3) * b, k_blocks=4, n_sink=1,
+                     n_local=1, c1=c1, c2=c2, kv_dtype="f32", flags=ap.AP_FLAG_PREDICTOR_FP32 if fp32 else 0)
+    rng = np.random.default_rng(H + c1)
+    blob = (rng.standard_normal(n_weight_floats(c1, c2)) * 0.3).astype(np.float32)
+    assert ctx.score_offset() == 0.0                    # nothing to report before the weights are set
+    ctx.set_weights(blob)
+    wts = orc.PredictorWeights.from_blob(blob, c1, c2)
+    ref = orc.predict(np.zeros((H, nb)), nb, wts)
+    off = ctx.score_offset()
+    assert abs(off - ref[nb // 2]) <= 1e-12 * max(1.0, abs(ref[nb // 2]))
+    hist = torch.zeros((n_inst, ctx.hist_slots(), nb + 3), dtype=torch.float32, device=dev)
+    pred = torch.full((n_inst, nb + 3), -5.0, dtype=torch.float32, device=dev)
+    pstate = torch.full((n_inst, nb + 3), 3.0, dtype=torch.float32, device=dev)
+    ws = torch.zeros((max(16, ctx.workspace_bytes()),), dtype=torch.uint8, device=dev)
+    for call in ("full", "rebase", "advance"):
+        if call == "full":
+            ctx.predict(hist, 7, nb, pred, ws)
+        else:
+            ctx.predict_incremental(hist, 7 if call == "rebase" else 8, nb, nb,
+                                    ap.AP_PRED_REBASE if call == "rebase" else ap.AP_PRED_ADVANCE, pstate, pred, ws)
+        torch.cuda.synchronize()
+        got = pred.cpu().numpy().astype(np.float64)
+        assert np.all(got[:, 1:nb - 1] == 0.0), call
+        assert_close(got[0, :nb] + off, ref, f"zero history, {call}")
 
 
 @pytest.mark.parametrize("H,nb0,c1,c2,n_steps,grow_every,fp32", [
@@ -224,11 +261,11 @@ def test_predict_incremental_tracks_oracle(H, nb0, c1, c2, n_steps, grow_every, 
         mode = ap.AP_PRED_REBASE if n == 0 else ap.AP_PRED_ADVANCE
         ctx.predict_incremental(hist, n, nb, nb_prev, mode, pstate, pred, ws)
         torch.cuda.synchronize()
-        got = pred.cpu().numpy().copy()
+        got = pred.cpu().numpy().astype(np.float64) + ctx.score_offset()
         if n % 7 == 3:
             ctx.predict_incremental(hist, n, nb, nb, ap.AP_PRED_HOLD, pstate, pred, ws)
             torch.cuda.synchronize()
-            again = pred.cpu().numpy()
+            again = pred.cpu().numpy().astype(np.float64) + ctx.score_offset()
             if nb == nb_prev:
                 assert np.array_equal(again[:, :nb], got[:, :nb]), f"HOLD changed the prediction at n={n}"
             else:   # the last columns came from the full-tile kernel in the first call
@@ -499,6 +536,7 @@ def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks
                 assert_close(run.row[i, :run.nb(t)].cpu().numpy(), ref, f"warm-up row {j} inst {i}")
     stats = ScoreStats()
     modes = stats.modes = []         # predictor mode of every step (0 = re-base, 1 = advance)
+    off = run.ctx.score_offset()     # pred is relative to the all-zero-history score
     for s in range(steps):
         t = w.t_at(s)
         nb = run.nb(t)
@@ -523,13 +561,13 @@ def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks
             n = pos[i]
             qi = to_f64(qs[n])
             ref_pred = orc.predict(before[n], nb, wts)
-            assert_close(pred[n, :nb], ref_pred, f"step {s} inst {i} pred")
+            assert_close(pred[n, :nb].astype(np.float64) + off, ref_pred, f"step {s} inst {i} pred")
             got_idx = idx[n, :cnt[n]]
             # decision in the kernel's precision: the oracle's selection on the kernel's fp32 scores
             exp_idx = orc.select_blocks(pred[n, :nb].astype(np.float64), nb, w.k_blocks, w.n_sink, w.n_local)
             assert got_idx.tolist() == exp_idx.tolist(), f"step {s} inst {i}: selection differs"
             # against the oracle's float64 scores: counted, and every swapped pair bounded by the score error
-            stats.add(f"step {s} inst {i}", pred[n, :nb].astype(np.float64), ref_pred, got_idx, nb, w.k_blocks,
+            stats.add(f"step {s} inst {i}", pred[n, :nb].astype(np.float64) + off, ref_pred, got_idx, nb, w.k_blocks,
                       w.n_sink, w.n_local)
             ref_out, A = orc.sparse_attention(qi, Kc[i], Vc[i], got_idx, b, t)
             for h in range(w.g):
@@ -544,11 +582,14 @@ def lockstep(w, dev, steps, sample, fused_every=2, incremental=True, warm_checks
 
 
 # Ceilings for the share of predicted picks that may differ from the selection on the oracle's float64 scores
-# (measured on the seeded workloads, with head-room; the counts are reproducible).  cfg0 has well separated
-# scores; cfg1-3 draw N(0,1)/sqrt(128) keys, whose attention is nearly uniform, so that blocks which were never
-# selected carry almost identical histories and their scores differ by less than fp32 resolves at the
-# magnitude of pred; cfg4's planted structure separates the blocks that matter.
-MISMATCH_CEILING = {"cfg0": 0.0, "cfg1": 1.0, "cfg2": 1.0, "cfg3": 1.0, "cfg4": 1.0, "small": 1.0}
+# (measured on the seeded workloads, with head-room; the counts are reproducible).  cfg0 and the small workloads
+# have well separated scores, and the fp32 predictor resolves every configuration.  cfg1-3 draw N(0,1)/sqrt(128)
+# keys, whose attention is nearly uniform: blocks that were never selected carry almost identical histories, the
+# gaps at the selection boundary go down to 1e-5 of the candidates' spread, and the f16-operand predictor
+# (error 2e-3 of the spread) resolves a few percent of the picks the other way.  cfg4's planted structure
+# separates the blocks that matter.  Measured: cfg1 4.0 %, cfg2 2.9 %, cfg3 1.2 %, cfg4 0.04 %.
+MISMATCH_CEILING = {"cfg0": 0.0, "cfg1": 0.08, "cfg1-fp32": 0.0, "cfg2": 0.06, "cfg3": 0.04, "cfg4": 0.005,
+                    "small": 0.01}
 
 
 def check_stats(name, st, key, rows=None):
@@ -609,7 +650,8 @@ def test_lockstep_cfg1_sampled_steps(fp32):
     ap = _ap()
     w = CONFIGS["cfg1"].with_(steps=6, calib_every=3)
     st = lockstep(w, dev, w.steps, sample=[0, 5], flags=ap.AP_FLAG_PREDICTOR_FP32 if fp32 else 0)
-    check_stats("cfg1 lock-step, " + ("fp32 predictor" if fp32 else "f16 MFMA predictor"), st, "cfg1", rows=12)
+    check_stats("cfg1 lock-step, " + ("fp32 predictor" if fp32 else "f16 MFMA predictor"), st,
+                "cfg1-fp32" if fp32 else "cfg1", rows=12)
 
 
 # --------------------------------------------------------------------------------------------- full-size configs
@@ -792,7 +834,8 @@ def test_lockstep_refresh_interval(every):
         for i in range(w.n_inst):
             qi = to_f64(q[i])
             if selects or predicts_always:                 # an advancing state stays current on every step
-                assert_close(pred[i, :nb], orc.predict(before[i], nb, wts), f"step {s} inst {i} pred")
+                assert_close(pred[i, :nb].astype(np.float64) + run.ctx.score_offset(), orc.predict(before[i], nb, wts),
+                             f"step {s} inst {i} pred")
             got_idx = idx[i, :cnt[i]]
             if selects:
                 exp_idx = orc.select_blocks(pred[i, :nb].astype(np.float64), nb, w.k_blocks, w.n_sink, w.n_local)
