@@ -81,17 +81,25 @@ __host__ __device__ constexpr int predictor_tap(int half, int out, int q) {
   return T[half][out][q];
 }
 
-// f16 operand table of the MFMA predictor variant (8/8 channels), built on the host by ap_set_weights:
-// [half 2][K-step 6][lane 64][8 f16], placed kMfmaTableFloatOffset floats into the weight buffer
-// (the fp32 section is 10*8 + 9*64 + 2*8 + 1 = 673 floats; 676 keeps 16-byte alignment).
-// It is followed by the layer-1 table [half 2][lane 64][8 f16]: row m = 8 q + c1, K slot k = 3 * xrow + kw,
-// scaled by 2^-4.
+// f16 operand tables of the MFMA incremental kernel for 8/8 channels, built on the host by ap_set_weights and
+// placed kMfmaTableFloatOffset floats into the weight buffer (the fp32 section is 10*8 + 9*64 + 2*8 + 1 = 673
+// floats; 676 keeps 16-byte alignment): layer 2 [half 2][K-step 6][lane 64][8 f16], then layer 1
+// [half 2][lane 64][8 f16]; what a lane's entries stand for is said in predict_inc8.h.
+//   layer 2  lane (m = 8 o + c2, h) of K-step s: entries e = 0..3 belong to the step's first (y1 row q, tap kw)
+//            pair, 4..7 to its second, input channel 4 h + e % 4; the pairs of step s are (ri_pair_q(s, 0), kw) and
+//            (ri_pair_q(s, 1), kw) with kw = ri_pair_kw(s): centre taps first (their operands are registers as
+//            they come out of layer 1), then the two outer taps
+//   layer 1  lane (m = 8 q + c1, h): entry e is K slot (h, e) = (staged x row ri_slot_row, tap ri_slot_kw); row -1
+//            is the constant 1, whose weight 2^8 min(b1, 0) is the accumulator start; weights scaled by 2^-4
+__host__ __device__ constexpr int ri_pair_q(int step, int second) { return 2 * (step & 1) + second; }
+__host__ __device__ constexpr int ri_pair_kw(int step) { return step < 2 ? 1 : (step < 4 ? 0 : 2); }
+__host__ __device__ constexpr int ri_slot_row(int h, int e) { return e < 6 ? (h ? 3 : 0) + (e & 1) : ((h && e == 7) ? -1 : 2); }
+__host__ __device__ constexpr int ri_slot_kw(int h, int e) { return e < 6 ? e / 2 : (h ? 2 : e - 6); }
 constexpr int kMfmaTableFloatOffset = 676;
 constexpr int kMfmaTableHalfs = 2 * 6 * 64 * 8 + 2 * 64 * 8;
 // ... and by the tables of the interior-state kernel (predict_interior.h): layer 2 [step 8][lane 64][8 f16],
 // layer 1 [lane 64][8 f16].
 constexpr int kMfmaInteriorTableHalfs = 8 * 64 * 8 + 64 * 8;
-
 // The same for 16/32 channels (fp32 section: 10*16 + 9*16*32 + 2*32 + 1 = 4833 floats):
 // layer 2 [half 2][pair 8][kw 3][lane 64][8 f16], lane (m = lane % 32, h = lane / 32) holding input channels
 // 8h..8h+7 of output channel m for the kernel row that pair (q, o) stands for; then layer 1

@@ -178,34 +178,37 @@ int ap_set_weights(ap_ctx* ctx, const float* blob, size_t n_floats, void* stream
   p += c2;
   p[0] = b3[0];
   if (mfma_table) {
-    // A operand of the 32x32x16 f16 MFMA: lane (m = lane % 32, h = lane / 32) of K-step s holds the 8
-    // input channels of K chunk 2s + h = (q, kw) for row m = 8 * out + c2 (rows 24..31 stay zero).
+    // Operands of the register-resident incremental kernel (layout and K-slot maps: predict_inc8.h).
     _Float16* t = reinterpret_cast<_Float16*>(packed.data() + ap::kMfmaTableFloatOffset);
     for (int half = 0; half < 2; ++half)
       for (int s = 0; s < 6; ++s)
         for (int lane = 0; lane < 64; ++lane) {
-          const int m = lane % 32, chunk = 2 * s + lane / 32, q = chunk / 3, kw = chunk % 3;
-          for (int ci = 0; ci < 8; ++ci) {
+          const int m = lane % 32, h = lane / 32, kw = ap::ri_pair_kw(s);
+          for (int e = 0; e < 8; ++e) {
+            const int q = ap::ri_pair_q(s, e / 4), ci = 4 * h + e % 4;
             float v = 0.f;
             if (m < 24) {
               const int kh = ap::predictor_tap(half, m / 8, q);
               if (kh >= 0) v = w2[(((size_t)(m % 8) * c1 + ci) * 3 + kh) * 3 + kw];
             }
-            t[((half * 6 + s) * 64 + lane) * 8 + ci] = (_Float16)v;
+            t[((half * 6 + s) * 64 + lane) * 8 + e] = (_Float16)v;
           }
         }
-    // Layer 1: lane (m = 8 q + c, h) holds K slots k = 8 h + e = 3 * xrow + kw over the five staged x rows.
-    // y1 row q of a half reads staged rows base .. base + 2; a tap row outside the history window is dropped.
+    // Layer 1: y1 row q of a half reads staged x rows base .. base + 2; a tap row outside the history window is
+    // dropped; the constant slot carries the accumulator start 2^8 min(b1, 0).
     _Float16* t1 = t + 2 * 6 * 64 * 8;
     for (int half = 0; half < 2; ++half)
       for (int lane = 0; lane < 64; ++lane)
         for (int e = 0; e < 8; ++e) {
-          const int m = lane % 32, k = 8 * (lane / 32) + e, q = m / 8, c = m % 8;
+          const int m = lane % 32, h = lane / 32, q = m / 8, c = m % 8;
+          const int xrow = ap::ri_slot_row(h, e), kw = ap::ri_slot_kw(h, e);
           const int base = (half == 0 && q == 3) ? 0 : q;
           const int zero_kh = q == 3 ? (half == 0 ? 0 : 2) : -1;
           float v = 0.f;
-          if (k < 15) {
-            const int kh = k / 3 - base, kw = k % 3;
+          if (xrow < 0) {
+            v = 256.f * (b1[c] < 0.f ? b1[c] : 0.f);
+          } else {
+            const int kh = xrow - base;
             if (kh >= 0 && kh < 3 && kh != zero_kh) v = w1[(c * 3 + kh) * 3 + kw] * (1.f / 16.f);
           }
           t1[(half * 64 + lane) * 8 + e] = (_Float16)v;

@@ -28,6 +28,7 @@
 // the state, so callers re-base with the full-tile kernel now and then.
 #include "predict_body.h"
 #include "predict_body16.h"
+#include "predict_inc8.h"
 #include "predict_interior.h"
 
 namespace ap {
@@ -145,8 +146,8 @@ __global__ __launch_bounds__(kPredThreads) void predict_full_kernel(const float*
 // Variants:
 //   VALU  fp32 FMAs, weights through scalar loads (any compiled channel pair; AP_FLAG_PREDICTOR_FP32);
 //   MFMA  both layers as 32x32x16 f16 MFMA chains with fp32 accumulation, 32 columns at a time:
-//         predict_inc_mfma_body (C1 = C2 = 8, predict_body.h) and predict_inc_mfma16_body (C1 = 16,
-//         C2 = 32, predict_body16.h).
+//         predict_inc_reg_body (C1 = C2 = 8, predict_inc8.h: both layers in registers) and
+//         predict_inc_mfma16_body (C1 = 16, C2 = 32, predict_body16.h: y1 through LDS).
 
 template <int C1, int C2, int HF>
 __device__ __forceinline__ void y2_valu(const Weights<C1, C2>& W, const float* yb, int YW, float (&o)[3][C2]) {
@@ -266,14 +267,12 @@ __global__ __launch_bounds__(2 * IW) void predict_inc_kernel(const float* __rest
 }
 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4)))   // four workgroups per CU: 128 VGPRs
-void predict_inc_mfma_kernel(const float* __restrict__ hist,
-                                                               const float* __restrict__ wts_global, int R, int H,
-                                                               int newest_slot, int nb_cur, int nb_cap, int inst0,
-                                                               int advance, float* __restrict__ pstate,
-                                                               float* __restrict__ pred) {
+void predict_inc_mfma_kernel(const float* __restrict__ hist, const float* __restrict__ wts_global, int R, int H,
+                             int newest_slot, int nb_cur, int nb_cap, int inst0, int advance,
+                             float* __restrict__ pstate, float* __restrict__ pred) {
   extern __shared__ __align__(16) float smem[];
-  predict_inc_mfma_body(hist, wts_global, R, H, newest_slot, nb_cur, nb_cap, inst0 + blockIdx.y, blockIdx.x, gridDim.x,
-                        advance, pstate, pred, smem);
+  predict_inc_reg_body(hist, wts_global, R, H, newest_slot, nb_cur, nb_cap, inst0 + blockIdx.y, blockIdx.x, gridDim.x,
+                       advance, pstate, pred, smem);
 }
 
 __global__ __launch_bounds__(256) void predict_inc_mfma16_kernel(const float* __restrict__ hist,
@@ -405,10 +404,10 @@ template <int C1, int C2>
 hipError_t run_inc(const Shape& s, int inst0, int ninst, const float* dweights, const float* hist, int newest_slot,
                    int nb_cur, int advance, float* pstate, float* pred, hipStream_t st) {
   if (C1 == 8 && C2 == 8 && s.predictor_mfma) {
-    const size_t lds = sizeof(float) * kPredMfmaLdsFloats;
-    const int tiles = (nb_cur + kPmIW - 1) / kPmIW;
+    const size_t lds = sizeof(float) * kPredRegLdsFloats;
+    const int blocks = (nb_cur + kRiOut - 1) / kRiOut;
     int chunks = (2048 + s.n_inst - 1) / s.n_inst;       // about eight workgroups per CU when instances are few
-    if (chunks > tiles) chunks = tiles;
+    if (chunks > (blocks + 3) / 4) chunks = (blocks + 3) / 4;   // at least a block per wave
     predict_inc_mfma_kernel<<<dim3(chunks, ninst), 256, lds, st>>>(
         hist, dweights, s.R, s.H, newest_slot, nb_cur, s.nb_cap, inst0, advance, pstate, pred);
     return hipGetLastError();

@@ -1,13 +1,14 @@
 // MFMA evaluation of the interior state of the incremental predictor from scratch (8/8 channels):
 //   state[j] = sum_{r=2}^{H-3} sum_c w3[c] * (relu(y2[c][r][j]) - relu(B2[c]))      (difference form, ap_internal.h)
 // i.e. what a re-base needs; the border rows 0, 1, H-2, H-1 and the head are then added by the incremental
-// kernel run without an advance.  Same arithmetic as predict_inc_mfma_body (f16 operands, x as hi + lo of 2^12 x,
-// fp32 accumulation, y1 kept as f16 of 2^8 y1), so a re-based state continues the advanced one without a step.
+// kernel run without an advance.  Same arithmetic as the incremental kernels (f16 operands - x as one f16 of
+// 2^12 x for 8/8 channels, as hi + lo for 16/32 -, fp32 accumulation, y1 kept as f16 of 2^8 d1), so a re-based
+// state continues the advanced one without a step.
 //
 // Rows 2..H-3 have no zero padding in time, so every row is the same contraction and the time axis is walked in
 // strips of three output rows:
 //   pass p    layer 1 for y1 rows 1+3p .. 3+3p from x rows 3p .. 3p+4: one 32-row MFMA block (3 rows x 8 channels,
-//             8 rows idle), K = 5 x rows x 3 taps (+1 unused), hi + lo
+//             8 rows idle), K = 5 x rows x 3 taps (+1 unused)
 //   strip s   layer 2 for output rows 2+3s .. 4+3s from y1 rows 1+3s .. 5+3s, i.e. the rows of passes s and s+1:
 //             rows = (3 outputs x 8 channels), K = 5 y1 rows x 3 taps x 8 channels = 15 chunks in 8 steps
 // A ring row beyond the newest one is some other finite row of the ring; it only reaches outputs beyond row H-3,
@@ -128,15 +129,13 @@ __device__ __forceinline__ void predict_interior_mfma_body(const float* __restri
     fetch();
     // One wave reads what it has just written: the LDS keeps a wave's accesses in order, the compiler has to as well.
     asm volatile("" ::: "memory");
-    uint4v whi, wlo;
+    uint4v whi;                                          // (the low halves of the staged words: x as one f16)
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
       const uint32_t wa = s_x[n + xoff[e]], wb = s_x[n + xoff[e + 1]];
       whi[e / 2] = __builtin_amdgcn_perm(wb, wa, 0x05040100u);
-      wlo[e / 2] = __builtin_amdgcn_perm(wb, wa, 0x07060302u);
     }
     float16v acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, __builtin_bit_cast(half8, whi), b1acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1, __builtin_bit_cast(half8, wlo), acc, 0, 0, 0);
     half8* dst = s_y1 + 3 * (p & 1) * YW + n;
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
