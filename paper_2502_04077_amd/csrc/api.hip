@@ -97,7 +97,7 @@ int ap_create(const ap_config* c, ap_ctx** out) {
     const size_t nblk = s.n_split == 1 ? s.k : (s.k + s.n_split - 1) / s.n_split;
     const size_t partials = (size_t)ap::kAttnWaves * s.g * s.d, tile = (size_t)ap::kAttnWaves * 8 * (2 * s.d + 16) / 4;
     const size_t attn = (size_t)s.g * nblk * s.b + (partials > tile ? partials : tile) + (size_t)s.g * nblk + 2 * nblk + 4 * s.g + 2 * (size_t)((s.nb_cap + 31) / 32);
-    const size_t comb = (size_t)s.n_split * s.g + (size_t)s.k;
+    const size_t comb = (size_t)s.n_split * s.g + 1024;     // (sparse_combine_kernel: scales + a chunk of the row)
     if (attn * sizeof(float) > 65536 || comb * sizeof(float) > 65536) { delete ctx; return AP_ERR_UNSUPPORTED; }
   }
   const int chunk_blocks = ap::kCalibChunkTokens / s.b;

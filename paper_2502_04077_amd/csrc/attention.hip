@@ -20,17 +20,23 @@ void sparse_decode_kernel(SparseArgs a) {
   sparse_decode_body<T, D, G, NW, PIECED>(a, a.inst0 + blockIdx.y, blockIdx.x, smem);
 }
 
-// Merges the splits of one instance: global (M, L) per head, normalised output, pooled row.
+// Merges the splits of one instance: global (M, L) per head, normalised output, pooled row.  The row is nb_cap
+// columns long (8K at a 128K context) and all but `cnt` of them are zero, so it is cut into chunks of
+// kCombineCols columns, one workgroup each (blockIdx.x = chunk, blockIdx.y = instance): the chunk is put together
+// in LDS - zeros, then the values of the listed blocks that fall into it - and written out whole and coalesced.
+// Every workgroup works out the split scales for itself (n_split x G values); chunk 0 also writes the output.
+constexpr int kCombineCols = 1024;
+
 template <int D, int G>
 __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs a) {
   extern __shared__ __align__(16) float smem[];
-  const int inst = a.inst0 + blockIdx.x;
+  const int inst = a.inst0 + blockIdx.y, chunk = blockIdx.x;
   const int cnt = min(max(a.cnt[inst], 0), a.k);
   float* s_scale = smem;                               // [n_split][G]  exp(m_s - M) / L
-  int* s_idx = reinterpret_cast<int*>(s_scale + a.n_split * G);   // [k]
+  float* s_row = s_scale + a.n_split * G;              // [kCombineCols]
+  const int c0 = chunk * kCombineCols, c1 = min(a.nb_cap, c0 + kCombineCols);
 
-  for (int j = threadIdx.x; j < cnt; j += kAttnThreads)
-    s_idx[j] = min(max(a.idx[(size_t)inst * a.k + j], 0), a.nb_cur - 1);
+  for (int j = threadIdx.x; j < c1 - c0; j += kAttnThreads) s_row[j] = 0.f;
   if (threadIdx.x < G) {
     const int h = threadIdx.x;
     const float* ml = a.part_ml + ((size_t)inst * a.n_split * G + h) * 2;
@@ -47,22 +53,30 @@ __global__ __launch_bounds__(kAttnThreads) void sparse_combine_kernel(SparseArgs
     for (int s = 0; s < a.n_split; ++s) s_scale[s * G + h] *= invL;
   }
   __syncthreads();
-  for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
-    const int h = o / D;
-    float v = 0.f;
-    for (int s = 0; s < a.n_split; ++s)
-      v = fmaf(a.part_acc[((size_t)inst * a.n_split + s) * G * D + o], s_scale[s * G + h], v);
-    a.out[(size_t)inst * G * D + o] = v;
+  if (chunk == 0) {
+    for (int o = threadIdx.x; o < G * D; o += kAttnThreads) {
+      const int h = o / D;
+      float v = 0.f;
+      for (int s = 0; s < a.n_split; ++s)
+        v = fmaf(a.part_acc[((size_t)inst * a.n_split + s) * G * D + o], s_scale[s * G + h], v);
+      a.out[(size_t)inst * G * D + o] = v;
+    }
   }
   // pooled probability of list position jb: max over heads of (block max relative to its split) * split scale
-  write_row(a.row + (size_t)inst * a.row_stride, a.nb_cap, s_idx, cnt, [&](int jb) {
-    const int s = jb / a.blk_per_split;
-    float mx = 0.f;
+  for (int jb = threadIdx.x; jb < cnt; jb += kAttnThreads) {
+    const int blk = min(max(a.idx[(size_t)inst * a.k + jb], 0), a.nb_cur - 1);
+    if (blk >= c0 && blk < c1) {
+      const int s = jb / a.blk_per_split;
+      float mx = 0.f;
 #pragma unroll
-    for (int h = 0; h < G; ++h)
-      mx = fmaxf(mx, a.part_bmp[((size_t)inst * G + h) * a.k + jb] * s_scale[s * G + h]);
-    return mx;
-  });
+      for (int h = 0; h < G; ++h)
+        mx = fmaxf(mx, a.part_bmp[((size_t)inst * G + h) * a.k + jb] * s_scale[s * G + h]);
+      s_row[blk - c0] = mx;                            // (a block listed twice: either of two equal values)
+    }
+  }
+  __syncthreads();
+  float* row = a.row + (size_t)inst * a.row_stride;
+  for (int j = threadIdx.x; j < c1 - c0; j += kAttnThreads) row[c0 + j] = s_row[j];
 }
 
 struct CalibArgs {
@@ -204,8 +218,8 @@ hipError_t run_sparse(const Shape& s, int ninst, SparseArgs a, hipStream_t st) {
   sparse_decode_kernel<T, D, G, kAttnWaves, false><<<dim3(a.n_split, ninst), kAttnThreads, lds, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.n_split == 1) return e;
-  const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G) + sizeof(int) * a.k;
-  sparse_combine_kernel<D, G><<<dim3(ninst), kAttnThreads, lds2, st>>>(a);
+  const size_t lds2 = sizeof(float) * ((size_t)a.n_split * G + kCombineCols);
+  sparse_combine_kernel<D, G><<<dim3((a.nb_cap + kCombineCols - 1) / kCombineCols, ninst), kAttnThreads, lds2, st>>>(a);
   return hipGetLastError();
 }
 

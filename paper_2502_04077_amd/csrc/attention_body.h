@@ -327,20 +327,6 @@ __device__ __forceinline__ void softmax_stats(float* s_p, int ld, int ntok, int 
   __syncthreads();
 }
 
-// Writes one instance's pooled row: value_at(pos) at column idx[pos] (idx ascending), 0 elsewhere.
-template <class ValueAt>
-__device__ __forceinline__ void write_row(float* __restrict__ row, int nb_cap, const int* s_idx, int cnt,
-                                          ValueAt value_at) {
-  for (int j = threadIdx.x; j < nb_cap; j += blockDim.x) {
-    int lo = 0, hi = cnt;                       // first position with idx >= j
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (s_idx[mid] < j) lo = mid + 1; else hi = mid;
-    }
-    row[j] = (lo < cnt && s_idx[lo] == j) ? value_at(lo) : 0.f;
-  }
-}
-
 constexpr int kSparseStage = 8;
 // Floats of the region shared by the staged K tile (phase 1) and the per-wave output partials (after phase 3).
 template <int D, int G, int NW> constexpr int sparse_acc_floats() {
