@@ -289,6 +289,57 @@ def test_predict_incremental_tracks_oracle(H, nb0, c1, c2, n_steps, grow_every, 
     print(f"incremental predictor worst relative error over {n_steps} un-rebased steps: {worst:.2e}")
 
 
+@pytest.mark.parametrize("c1,c2", [(8, 8), (16, 32)])
+def test_predict_stress_large_weights(c1, c2):
+    """Weights five times the workloads' (sigma 0.5) on rows with entries up to 1: the f16-operand kernels still
+    have to stay within the 1e-3 bar.  Bound by the arithmetic: an f16 operand carries a relative rounding of at
+    most 2^-11, the products are exact and summed in fp32, so the variable part of a score is off by about
+    2^-11 x sqrt(2) per operand pair, averaged down over the 72 to 144 taps and H rows; the result here is a few
+    1e-4 of max|pred| for 8/8 and for 16/32 channels."""
+    dev = _dev()
+    ap = _ap()
+    H, nb, n_inst, b = 64, 200, 2, 16
+    nb_cap = nb + 4
+    ctx = ap.Context(n_inst=n_inst, g=1, head_dim=64, block=b, hist_len=H, t_cap=nb_cap * b, k_blocks=4, n_sink=1,
+                     n_local=1, c1=c1, c2=c2, kv_dtype="f32")
+    R = ctx.hist_slots()
+    rng = np.random.default_rng(c1 * 100 + c2)
+    blob = (rng.standard_normal(n_weight_floats(c1, c2)) * 0.5).astype(np.float32)
+    ctx.set_weights(blob)
+    wts = orc.PredictorWeights.from_blob(blob, c1, c2)
+    off = ctx.score_offset()
+    hist = torch.zeros((n_inst, R, nb_cap), dtype=torch.float32, device=dev)
+    row = torch.zeros((n_inst, nb_cap), dtype=torch.float32, device=dev)
+    pred = torch.zeros((n_inst, nb_cap), dtype=torch.float32, device=dev)
+    pstate = torch.zeros((n_inst, nb_cap), dtype=torch.float32, device=dev)
+    ws = torch.zeros((max(16, ctx.workspace_bytes()),), dtype=torch.uint8, device=dev)
+    logical = np.zeros((n_inst, H, nb_cap))
+    worst = 0.0
+    for n in range(H + 24):
+        r = np.zeros((n_inst, nb_cap), dtype=np.float32)
+        r[:, :nb] = (rng.random((n_inst, nb)) ** 2).astype(np.float32)
+        row.copy_(torch.from_numpy(r))
+        ctx.update_history(hist, n, row)
+        for i in range(n_inst):
+            logical[i] = orc.history_push(logical[i], r[i].astype(np.float64))
+        if n < H - 1:
+            continue
+        mode = ap.AP_PRED_REBASE if n == H - 1 else ap.AP_PRED_ADVANCE
+        ctx.predict_incremental(hist, n + 1, nb, nb, mode, pstate, pred, ws)
+        torch.cuda.synchronize()
+        got = pred.cpu().numpy().astype(np.float64) + off
+        for i in range(n_inst):
+            ref = orc.predict(logical[i], nb, wts)
+            assert_close(got[i, :nb], ref, f"({c1},{c2}) sigma 0.5, row {n} inst {i}")
+            worst = max(worst, np.abs(got[i, :nb] - ref).max() / np.abs(ref).max())
+    ctx.predict(hist, H + 24, nb, pred, ws)
+    torch.cuda.synchronize()
+    full = pred.cpu().numpy().astype(np.float64) + off
+    for i in range(n_inst):
+        assert_close(full[i, :nb], orc.predict(logical[i], nb, wts), f"({c1},{c2}) sigma 0.5, full tile inst {i}")
+    print(f"({c1},{c2}) predictor, sigma 0.5 weights: worst error {worst:.2e} of max|pred|")
+
+
 # --------------------------------------------------------------------------------------------- attention
 ATTN_CASES = [
     # name, kwargs, t_cur, n_inst hint
