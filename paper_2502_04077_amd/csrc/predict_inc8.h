@@ -53,6 +53,11 @@ template <int CTRL> __device__ __forceinline__ uint32_t dpp_all(uint32_t v) {
 }
 constexpr int kWaveShr1 = 0x138, kWaveShl1 = 0x130;     // lane l reads lane l - 1 / l + 1 of the whole wave
 
+// One float at a 32-bit byte offset from a wave-uniform row pointer (scalar base + vector offset addressing).
+__device__ __forceinline__ float ld_row(const float* row, uint32_t byte_off) {
+  return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + byte_off);
+}
+
 // Workgroup `chunk` of `n_chunks` of instance `inst` (256 threads); smem: kPredRegLdsFloats floats.
 __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ hist, const float* __restrict__ wts_global,
                                                      int R, int H, int newest_slot, int nb_cur, int nb_cap, int inst,
@@ -103,13 +108,13 @@ __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ h
   const float inv_H = 1.f / (float)H;                    // the time mean as a multiplication
   constexpr float kUnscale = 1.f / kAccScale;            // the head sums come out times 2^8 (exact to undo)
   // Ring rows of the ten staged x rows: staged rows 0..4 of the top half are history rows -1..3, of the bottom
-  // half H-5..H-1.
-  int row_off[2][5];
+  // half H-5..H-1.  (Wave-uniform pointers: they live in scalar registers.)
+  const float* row_base[2][5];
 #pragma unroll
   for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
     for (int r = 0; r < 5; ++r)
-      row_off[h2][r] = __builtin_amdgcn_readfirstlane(ring_slot(newest_slot, H, R, h2 ? H - 5 + r : r - 1) * nb_cap);
+      row_base[h2][r] = hist_inst + (size_t)__builtin_amdgcn_readfirstlane(ring_slot(newest_slot, H, R, h2 ? H - 5 + r : r - 1)) * nb_cap;
   uint32_t* s_x01 = reinterpret_cast<uint32_t*>(smem);   // [half][lane half][column]: (row 0 | row 1) or (row 3 | row 4)
   uint32_t* s_x2 = s_x01 + 2 * 2 * kRiStageCols;         // [half][lane half][column]: row 2 (col - 1 | col) or (col + 1 | 1)
   float2* s_part = reinterpret_cast<float2*>(smem + kRiStageWords);   // [half][column]: (moving, border)
@@ -132,38 +137,42 @@ __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ h
     for (int i = 0; i < kPerThread; ++i) pst[i] = pstate_inst[min(col0 + tid + 256 * i, nb_cur - 1)];
 
     // Stage the x rows of history columns col0 - 4 .. col0 + kRiPassCols + 3 (zero outside the tile): thread tid
-    // takes column tid of each chunk of 256, once per half; all loads are issued before the first is used.
+    // takes column tid of each chunk of 256, once per half; all loads are issued before the first is used.  A row
+    // is addressed as a wave-uniform base plus a 32-bit byte offset, the column offsets are shared by the ten
+    // rows, and no load is predicated: a thread past the staged range repeats its last column (every address is
+    // inside the tile) and writes the copy to a staging slot that no block reads.
     {
       constexpr int kChunks = (kRiStageCols + 255) / 256;
       float xv[2][kChunks][7];
+      float sc[kChunks], sm[kChunks], sp[kChunks];
 #pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2)
+      for (int ch = 0; ch < kChunks; ++ch) {
+        const int c = col0 - 4 + min(ch * 256 + tid, n_stage - 1);
+        const uint32_t oc = (uint32_t)min(max(c, 0), nb_cur - 1) * 4u;
+        const uint32_t om = (uint32_t)min(max(c - 1, 0), nb_cur - 1) * 4u;
+        const uint32_t op = (uint32_t)min(max(c + 1, 0), nb_cur - 1) * 4u;
+        sc[ch] = (uint32_t)c < (uint32_t)nb_cur ? kXScale : 0.f;
+        sm[ch] = (uint32_t)(c - 1) < (uint32_t)nb_cur ? kXScale : 0.f;
+        sp[ch] = (uint32_t)(c + 1) < (uint32_t)nb_cur ? kXScale : 0.f;
 #pragma unroll
-        for (int ch = 0; ch < kChunks; ++ch) {
-          const int c = col0 - 4 + ch * 256 + tid;
-          const int cc = min(max(c, 0), nb_cur - 1), cm = min(max(c - 1, 0), nb_cur - 1), cp = min(max(c + 1, 0), nb_cur - 1);
+        for (int h2 = 0; h2 < 2; ++h2) {
 #pragma unroll
-          for (int r = 0; r < 7; ++r) xv[h2][ch][r] = 0.f;
-          if (ch * 256 + tid < n_stage) {
-#pragma unroll
-            for (int r = 0; r < 5; ++r) xv[h2][ch][r] = hist_inst[row_off[h2][r] + cc];
-            xv[h2][ch][5] = hist_inst[row_off[h2][2] + cm];
-            xv[h2][ch][6] = hist_inst[row_off[h2][2] + cp];
-          }
+          for (int r = 0; r < 5; ++r) xv[h2][ch][r] = ld_row(row_base[h2][r], oc);
+          xv[h2][ch][5] = ld_row(row_base[h2][2], om);
+          xv[h2][ch][6] = ld_row(row_base[h2][2], op);
         }
+      }
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
         for (int ch = 0; ch < kChunks; ++ch) {
-          const int i = ch * 256 + tid, c = col0 - 4 + i;
-          const float sc = (c >= 0 && c < nb_cur) ? kXScale : 0.f;
-          const float sm = (c >= 1 && c <= nb_cur) ? kXScale : 0.f, sp = (c >= -1 && c < nb_cur - 1) ? kXScale : 0.f;
+          const int i = ch * 256 + tid;
           const float* x = xv[h2][ch];
-          const half2v a01 = {(_Float16)(x[0] * sc), (_Float16)(x[1] * sc)};
-          const half2v a34 = {(_Float16)(x[3] * sc), (_Float16)(x[4] * sc)};
-          const half2v a2l = {(_Float16)(x[5] * sm), (_Float16)(x[2] * sc)};
-          const half2v a2r = {(_Float16)(x[6] * sp), (_Float16)1};
-          if (i < n_stage) {
+          const half2v a01 = {(_Float16)(x[0] * sc[ch]), (_Float16)(x[1] * sc[ch])};
+          const half2v a34 = {(_Float16)(x[3] * sc[ch]), (_Float16)(x[4] * sc[ch])};
+          const half2v a2l = {(_Float16)(x[5] * sm[ch]), (_Float16)(x[2] * sc[ch])};
+          const half2v a2r = {(_Float16)(x[6] * sp[ch]), (_Float16)1};
+          if (i < kRiStageCols) {
             s_x01[(h2 * 2 + 0) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a01);
             s_x01[(h2 * 2 + 1) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a34);
             s_x2[(h2 * 2 + 0) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a2l);
