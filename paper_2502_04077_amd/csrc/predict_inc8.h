@@ -38,20 +38,31 @@ namespace ap {
 namespace {
 
 constexpr int kRiOut = 28;                              // outputs per 32-column block
-constexpr int kRiPassBlocks = 18;                       // most blocks whose halves meet in one pass
-constexpr int kRiPassCols = kRiOut * kRiPassBlocks;     // 504 output columns per pass
-constexpr int kRiStageCols = kRiPassCols + 8;           // staged history columns: four more on either side (512)
-// LDS words: staged x operands [x01 | x2][half 2][lane half 2][kRiStageCols]; the partial sums
-// [half][column of the pass][moving | border]
+constexpr int kRiPassBlocks = 15;                       // most blocks whose halves meet in one pass
+constexpr int kRiPassCols = kRiOut * kRiPassBlocks;     // 420 output columns per pass
+constexpr int kRiStageCols = kRiPassCols + 8;           // staged history columns: four more on either side (428)
+constexpr int kRiRawSegs = (kRiStageCols + kWave - 1) / kWave;   // a raw history row arrives in wave-wide pieces (7)
+constexpr int kRiRawStride = kRiRawSegs * kWave;        // floats per raw row in LDS (448)
+// LDS words: the ten raw history rows of the next pass [row][kRiRawStride]; staged x operands
+// [x01 | x2][half 2][lane half 2][kRiStageCols]; the partial sums [half][column of the pass][moving | border]
+constexpr int kRiRawWords = 10 * kRiRawStride;
 constexpr int kRiStageWords = 2 * 2 * 2 * kRiStageCols;
 constexpr int kRiPartWords = 2 * kRiPassCols * 2;
-constexpr int kPredRegLdsFloats = kRiStageWords + kRiPartWords;
+constexpr int kPredRegLdsFloats = kRiRawWords + kRiStageWords + kRiPartWords;
 
 // Every lane is written (a lane without a source lane gets 0), so no previous value has to be set up.
 template <int CTRL> __device__ __forceinline__ uint32_t dpp_all(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, true);
 }
 constexpr int kWaveShr1 = 0x138, kWaveShl1 = 0x130;     // lane l reads lane l - 1 / l + 1 of the whole wave
+
+// 64 consecutive floats of LDS starting at `dst` (wave-uniform) are filled from global memory, lane l from
+// row[byte_off / 4] of its own choosing, without passing through registers; completion is counted by vmcnt.
+__device__ __forceinline__ void load_to_lds(const float* row, uint32_t byte_off, float* dst) {
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  __builtin_amdgcn_global_load_lds((gptr_t)(reinterpret_cast<const char*>(row) + byte_off), (lptr_t)dst, 4, 0, 0);
+}
 
 // One float at a 32-bit byte offset from a wave-uniform row pointer (scalar base + vector offset addressing).
 __device__ __forceinline__ float ld_row(const float* row, uint32_t byte_off) {
@@ -115,72 +126,79 @@ __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ h
 #pragma unroll
     for (int r = 0; r < 5; ++r)
       row_base[h2][r] = hist_inst + (size_t)__builtin_amdgcn_readfirstlane(ring_slot(newest_slot, H, R, h2 ? H - 5 + r : r - 1)) * nb_cap;
-  uint32_t* s_x01 = reinterpret_cast<uint32_t*>(smem);   // [half][lane half][column]: (row 0 | row 1) or (row 3 | row 4)
+  float* s_raw = smem;                                   // [staged row of top half 0..4 | of bottom half 0..4][kRiRawStride]
+  uint32_t* s_x01 = reinterpret_cast<uint32_t*>(smem + kRiRawWords);   // [half][lane half][column]: (row 0 | row 1) or (row 3 | row 4)
   uint32_t* s_x2 = s_x01 + 2 * 2 * kRiStageCols;         // [half][lane half][column]: row 2 (col - 1 | col) or (col + 1 | 1)
-  float2* s_part = reinterpret_cast<float2*>(smem + kRiStageWords);   // [half][column]: (moving, border)
+  float2* s_part = reinterpret_cast<float2*>(smem + kRiRawWords + kRiStageWords);   // [half][column]: (moving, border)
   const uint32_t* my_x01 = s_x01 + (hf * 2 + hsel) * kRiStageCols + n;
   const uint32_t* my_x2 = s_x2 + (hf * 2 + hsel) * kRiStageCols + n;
 
   // Passes of equal length, as few as the LDS allows.
   const int n_pass = (b_end - b_begin + kRiPassBlocks - 1) / kRiPassBlocks;
   const int pass_blocks = (b_end - b_begin + n_pass - 1) / n_pass;
+  // The raw rows of a pass are asked for a whole pass ahead and go straight to LDS: wave w brings pieces w and
+  // w + 4 of each of the ten rows (every address is clamped into the tile; what lies outside is masked when the
+  // rows are converted).
+  auto fetch_pass = [&](int pb) __attribute__((always_inline)) {
+    const int col0 = pb * kRiOut;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int k = wave + 4 * kk;
+      if (k < kRiRawSegs) {                                // (wave-uniform)
+        const uint32_t off = (uint32_t)min(max(col0 - 4 + k * kWave + lane, 0), nb_cur - 1) * 4u;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+          for (int r = 0; r < 5; ++r) load_to_lds(row_base[h2][r], off, s_raw + (h2 * 5 + r) * kRiRawStride + k * kWave);
+      }
+    }
+  };
+  fetch_pass(b_begin);
+  __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): this wave's pieces of the first pass are in LDS
 #pragma unroll 1
   for (int pb = b_begin; pb < b_end; pb += pass_blocks) {
     const int pe = min(b_end, pb + pass_blocks);
-    const int n_stage = (pe - pb) * kRiOut + 8;          // history columns to stage
     const int col0 = pb * kRiOut;                        // first output column of the pass
     const int col_end = min(nb_cur, pe * kRiOut);
-    // The state of this thread's columns is asked for now and used after the second barrier.
-    constexpr int kPerThread = (kRiPassCols + 255) / 256;
-    float pst[kPerThread];
-#pragma unroll
-    for (int i = 0; i < kPerThread; ++i) pst[i] = pstate_inst[min(col0 + tid + 256 * i, nb_cur - 1)];
-
-    // Stage the x rows of history columns col0 - 4 .. col0 + kRiPassCols + 3 (zero outside the tile): thread tid
-    // takes column tid of each chunk of 256, once per half; all loads are issued before the first is used.  A row
-    // is addressed as a wave-uniform base plus a 32-bit byte offset, the column offsets are shared by the ten
-    // rows, and no load is predicated: a thread past the staged range repeats its last column (every address is
-    // inside the tile) and writes the copy to a staging slot that no block reads.
+    // Every wave has seen its own pieces of this pass's raw rows arrive (before the loop, or before the last
+    // barrier of the pass before).
+    __syncthreads();
+    // Raw rows -> the words a lane's K slots are made of: x scaled by 2^12 and rounded to f16, zero outside the
+    // tile.  Thread tid takes staged columns tid and tid + 256.
     {
       constexpr int kChunks = (kRiStageCols + 255) / 256;
-      float xv[2][kChunks][7];
-      float sc[kChunks], sm[kChunks], sp[kChunks];
 #pragma unroll
       for (int ch = 0; ch < kChunks; ++ch) {
-        const int c = col0 - 4 + min(ch * 256 + tid, n_stage - 1);
-        const uint32_t oc = (uint32_t)min(max(c, 0), nb_cur - 1) * 4u;
-        const uint32_t om = (uint32_t)min(max(c - 1, 0), nb_cur - 1) * 4u;
-        const uint32_t op = (uint32_t)min(max(c + 1, 0), nb_cur - 1) * 4u;
-        sc[ch] = (uint32_t)c < (uint32_t)nb_cur ? kXScale : 0.f;
-        sm[ch] = (uint32_t)(c - 1) < (uint32_t)nb_cur ? kXScale : 0.f;
-        sp[ch] = (uint32_t)(c + 1) < (uint32_t)nb_cur ? kXScale : 0.f;
+        const int i = ch * 256 + tid;
+        if (i < kRiStageCols) {
+          const int c = col0 - 4 + i;
+          const float sc = (uint32_t)c < (uint32_t)nb_cur ? kXScale : 0.f;
+          const float sm = (uint32_t)(c - 1) < (uint32_t)nb_cur ? kXScale : 0.f;
+          const float sp = (uint32_t)(c + 1) < (uint32_t)nb_cur ? kXScale : 0.f;
+          const int im = max(i - 1, 0);
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-#pragma unroll
-          for (int r = 0; r < 5; ++r) xv[h2][ch][r] = ld_row(row_base[h2][r], oc);
-          xv[h2][ch][5] = ld_row(row_base[h2][2], om);
-          xv[h2][ch][6] = ld_row(row_base[h2][2], op);
-        }
-      }
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-        for (int ch = 0; ch < kChunks; ++ch) {
-          const int i = ch * 256 + tid;
-          const float* x = xv[h2][ch];
-          const half2v a01 = {(_Float16)(x[0] * sc[ch]), (_Float16)(x[1] * sc[ch])};
-          const half2v a34 = {(_Float16)(x[3] * sc[ch]), (_Float16)(x[4] * sc[ch])};
-          const half2v a2l = {(_Float16)(x[5] * sm[ch]), (_Float16)(x[2] * sc[ch])};
-          const half2v a2r = {(_Float16)(x[6] * sp[ch]), (_Float16)1};
-          if (i < kRiStageCols) {
+          for (int h2 = 0; h2 < 2; ++h2) {
+            const float* x = s_raw + h2 * 5 * kRiRawStride;
+            const half2v a01 = {(_Float16)(x[i] * sc), (_Float16)(x[kRiRawStride + i] * sc)};
+            const half2v a34 = {(_Float16)(x[3 * kRiRawStride + i] * sc), (_Float16)(x[4 * kRiRawStride + i] * sc)};
+            const half2v a2l = {(_Float16)(x[2 * kRiRawStride + im] * sm), (_Float16)(x[2 * kRiRawStride + i] * sc)};
+            const half2v a2r = {(_Float16)(x[2 * kRiRawStride + i + 1] * sp), (_Float16)1};
             s_x01[(h2 * 2 + 0) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a01);
             s_x01[(h2 * 2 + 1) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a34);
             s_x2[(h2 * 2 + 0) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a2l);
             s_x2[(h2 * 2 + 1) * kRiStageCols + i] = __builtin_bit_cast(uint32_t, a2r);
           }
         }
+      }
     }
     __syncthreads();
+    // The raw rows are free again: the next pass's loads, and the state of this thread's columns, are asked for
+    // now and have the block loop to arrive in.
+    if (pb + pass_blocks < b_end) fetch_pass(pb + pass_blocks);
+    constexpr int kPerThread = (kRiPassCols + 255) / 256;
+    float pst[kPerThread];
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) pst[i] = pstate_inst[min(col0 + tid + 256 * i, nb_cur - 1)];
 
     // One block.  BORDER: the block reaches beyond the tile, where x is zero and y1 = 0 (d1 = lo1); the other
     // blocks skip those selects.
@@ -247,6 +265,7 @@ __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ h
       if (b == 0 || b * kRiOut + 30 > nb_cur) block(b, std::true_type{});   // (the same for the whole wave)
       else block(b, std::false_type{});
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's pieces of the next pass are in LDS
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
