@@ -7,10 +7,10 @@
 // supplies row / column l % 32 and K entries 8 (l / 32) .. + 7 and receives D rows 8 (v / 4) + 4 (l / 32) + v % 4
 // (v = 0..15) of column l % 32.  What makes the registers enough:
 //   layer 1  rows = (staged y1 row q, channel c1), K = 16 = 15 (x row, tap) pairs + a constant 1 that carries the
-//            accumulator start.  The ten history rows of a pass of columns are fetched by the whole workgroup at
-//            the start of the pass (every load of the pass is in flight at once: with a load or two per block the
-//            kernel waited for memory, not for arithmetic), scaled by 2^12, rounded to f16 and left in LDS as the
-//            words a lane's K slots are made of, so that an operand is four 4-byte LDS reads and no arithmetic.
+//            accumulator start.  The ten history rows of a pass of columns go from global memory straight to LDS
+//            (global_load_lds, no registers), asked for a whole pass ahead; at the start of the pass they are
+//            converted once - scaled by 2^12, rounded to f16 - into the words a lane's K slots are made of, so
+//            that an operand is four 4-byte LDS reads and no arithmetic.
 //   layer 2  the result of layer 1 is, per lane, channels 4h .. 4h+3 of the four y1 rows of its own column: exactly
 //            half of the K entries of a layer-2 step whose 16 entries are two (y1 row, tap) pairs of 8 channels.
 //            The centre tap takes those registers as they are, the outer taps the same registers moved by one
@@ -20,12 +20,12 @@
 // Columns next to the ends of the 32 get wrong neighbours, so a block yields 28 outputs (lanes 2..29) and blocks
 // overlap by four columns.  All arithmetic is in the difference form of ap_internal.h: accumulators start at
 // 2^8 init, the ReLUs are clamps at 2^8 lo, y1 is kept as f16 of 2^8 d1.  f16 operands, fp32 accumulation.
-// Measured alternatives that came out within 3 % of this form at cfg2's shape (all about 84 us, of which 38 us is
-// the history traffic at HBM speed and 63 us the arithmetic, overlapping only in part): the outer taps through a
+// Measured alternatives that came out within 3 % of their baseline at cfg2's shape: the outer taps through a
 // wave-private piece of LDS instead of DPP moves, the head as a third MFMA on the clamped f16 result, a load or
-// two per block instead of a staged pass, five waves per SIMD instead of four, staggered first passes.
+// two per block instead of a staged pass, five waves per SIMD instead of four, staggered first passes.  What did
+// pay: no 64-bit address arithmetic or predication on the pass's loads, and the loads a pass ahead.
 // The two halves of a column meet once per pass of up to kRiPassCols columns, through LDS: the state and pred
-// are written by a short epilogue after the pass's second barrier.  The leaving row is evaluated by the same instruction
+// are written by a short epilogue after the pass's last barrier.  The leaving row is evaluated by the same instruction
 // sequence on the same values as when it entered (both halves run this code, and a block always covers the same
 // columns), so it cancels exactly.
 #pragma once
