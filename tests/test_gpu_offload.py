@@ -136,6 +136,35 @@ def test_prefetch_refuses_pageable_host_memory():
     assert rc == ap.AP_ERR_ARG
 
 
+def test_cache_pointer_is_checked_on_every_call():
+    """A cache pointer that was accepted once earns nothing: the same context is handed pinned memory (accepted),
+    then pageable memory (refused), then the pinned buffer again (accepted), then - after that buffer has been
+    released - pageable memory once more (refused).  Every refusal happens on the host, before any launch."""
+    dev = _dev()
+    ap = _ap()
+    ctx = ap.Context(n_inst=1, g=1, head_dim=64, block=16, hist_len=8, t_cap=64, k_blocks=2, n_sink=1, n_local=1,
+                     c1=4, c2=4, kv_dtype="f32")
+    lib = ap.load_library()
+    q = torch.zeros((1, 1, 64), device=dev)
+    row = torch.zeros((1, ctx.nb_cap()), device=dev)
+    ws = torch.zeros((max(16, ctx.workspace_bytes()),), dtype=torch.uint8, device=dev)
+
+    def calibrate(K):
+        return lib.ap_calibrate(ctx._h, q.data_ptr(), K.data_ptr(), 40, row.data_ptr(), ws.data_ptr(), None)
+
+    pinned = torch.zeros((1, 64, 64), pin_memory=True)
+    pageable = torch.zeros((1, 64, 64))
+    assert calibrate(pinned) == ap.AP_OK
+    assert calibrate(pageable) == ap.AP_ERR_ARG
+    assert calibrate(pinned) == ap.AP_OK
+    torch.cuda.synchronize()
+    del pinned
+    assert calibrate(pageable) == ap.AP_ERR_ARG
+    on_device = torch.zeros((1, 64, 64), device=dev)
+    assert calibrate(on_device) == ap.AP_OK
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("single_calls", [False, True])
 def test_offload_lockstep_vs_oracle(single_calls):
     """Every step of the prefetching schedule against the oracle started from the GPU's own history; once through
