@@ -83,7 +83,7 @@ __device__ __forceinline__ uint32_t split_hi_lo(float xv) {
   return __builtin_bit_cast(uint32_t, pr);
 }
 
-// Geometry shared by the MFMA variants: 124 output columns per tile; x columns c0-2 .. c0+125 (128) and y1
+// Tile geometry of the incremental MFMA kernel for 16/32 channels: 124 output columns per tile; x columns c0-2 .. c0+125 (128) and y1
 // columns c0-1 .. c0+126 (128) are staged, of which outputs 0..123 use x columns 0..127 and y1 columns 0..125.
 // The two surplus columns of each MFMA block read past their row into finite values and feed only outputs
 // that are dropped.
