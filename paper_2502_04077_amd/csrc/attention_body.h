@@ -434,11 +434,11 @@ __device__ __forceinline__ void sparse_decode_body(const SparseArgs& a, int inst
     qk_logits<T, D, G, kSparseStage, NW>(q_inst, K_inst, a.b, a.log2b, a.t_cur, ntok,
                                          [&](int jb) { return s_idx[p0 + jb]; },
                                          [&](int jb) { return s_phys[p0 + jb]; }, s_p, ld, s_acc);
-    // The V rows of this wave's first 16-token group do not depend on the probabilities: with PIECED (all
-    // workgroups of the launch resident and in step, so nobody else fills the gap) they are requested before
-    // the softmax pass and arrive while it runs - where the registers allow it (with g = 4 the kernel is at its
-    // 128 VGPRs already and would spill: 0.201 vs 0.183 ms at cfg2; with g = 1 it gains 1.5 % at cfg4).
-    constexpr bool kEarlyV = PIECED && G <= 2;
+    // The V rows of this wave's first 16-token group do not depend on the probabilities: they are requested before
+    // the softmax pass and arrive while it runs - where the registers allow it.  The pieced forms with g = 4 are at
+    // their 128 VGPRs already and would spill (0.201 vs 0.183 ms at cfg2); with g <= 2 they gain 1.5 % at cfg4, and
+    // the four-wave form, which has registers to spare, 2 % at cfg3.
+    constexpr bool kEarlyV = (PIECED && G <= 2) || !PIECED;
     const int ngroups = (ntok + kGroupTokens - 1) / kGroupTokens;
     uint4 vw[NL];
     auto load_v = [&](int grp) __attribute__((always_inline)) {
