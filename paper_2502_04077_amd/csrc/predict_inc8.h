@@ -141,10 +141,11 @@ __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ h
   // rows are converted).
   auto fetch_pass = [&](int pb) __attribute__((always_inline)) {
     const int col0 = pb * kRiOut;
+    const int n_cols = (min(b_end, pb + pass_blocks) - pb) * kRiOut + 8;   // staged columns of that pass
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
       const int k = wave + 4 * kk;
-      if (k < kRiRawSegs) {                                // (wave-uniform)
+      if (k < kRiRawSegs && k * kWave <= n_cols) {         // (wave-uniform; the conversion reads one column past the staged ones)
         const uint32_t off = (uint32_t)min(max(col0 - 4 + k * kWave + lane, 0), nb_cur - 1) * 4u;
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2)
@@ -170,7 +171,7 @@ __device__ __forceinline__ void predict_inc_reg_body(const float* __restrict__ h
 #pragma unroll
       for (int ch = 0; ch < kChunks; ++ch) {
         const int i = ch * 256 + tid;
-        if (i < kRiStageCols) {
+        if (i < (pe - pb) * kRiOut + 8) {                  // the staged columns of this pass
           const int c = col0 - 4 + i;
           const float sc = (uint32_t)c < (uint32_t)nb_cur ? kXScale : 0.f;
           const float sm = (uint32_t)(c - 1) < (uint32_t)nb_cur ? kXScale : 0.f;
