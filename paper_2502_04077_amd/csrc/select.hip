@@ -85,6 +85,8 @@ hipError_t launch_select(const Shape& s, int inst0, int ninst, const float* pred
   if (ninst <= 512 && n_mid > 4 * kSelThreads) {
     if (n_mid <= 4 * kSelThreadsWide) AP_SELECT_NT(4, kSelThreadsWide);
     else if (n_mid <= 8 * kSelThreadsWide) AP_SELECT_NT(8, kSelThreadsWide);
+    else if (n_mid <= 9 * kSelThreadsWide) AP_SELECT_NT(9, kSelThreadsWide);     // (a 128K context that has grown a little)
+    else if (n_mid <= 12 * kSelThreadsWide) AP_SELECT_NT(12, kSelThreadsWide);
     else if (n_mid <= 16 * kSelThreadsWide) AP_SELECT_NT(16, kSelThreadsWide);
     else AP_SELECT_NT(0, kSelThreadsWide);
   }

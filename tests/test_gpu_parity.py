@@ -113,6 +113,8 @@ def small(name="t", **kw):
     (2051, 64, 4, 4, "ties", 600), (2400, 64, 4, 4, "normal", 520), (8200, 128, 4, 4, "ties", 513),
     (9000, 64, 4, 4, "normal", 515), (5000, 128, 4, 4, "ties", 3), (12000, 200, 1, 1, "normal", 2),
     (20000, 64, 4, 4, "ties", 2), (4104, 64, 4, 4, "allequal", 1),
+    (8210, 128, 4, 4, "normal", 5), (9100, 128, 4, 4, "ties", 7), (9224, 64, 4, 4, "allequal", 3),
+    (9225, 64, 4, 4, "normal", 3),
 ])
 def test_select_topk_bit_exact(nb, k, ns, nl, mode, n_inst):
     dev = _dev()
