@@ -8,8 +8,7 @@ history, so that replaying it is idempotent (the pushed row lands in the same ri
 import pytest
 import torch
 
-from workloads import kv_cache, predictor_weights, queries
-from tests.test_gpu_parity import small
+from workloads import Workload, kv_cache, predictor_weights, queries
 
 pytestmark = pytest.mark.gpu
 
@@ -22,7 +21,11 @@ def test_step_and_calibration_replay_from_a_graph(kw):
     dev = torch.device("cuda:0")
     from paper_2502_04077_amd.runner import DecodeRun
     from paper_2502_04077_amd.binding import AP_PRED_REBASE
-    w = small("graph", g=4, head_dim=128, hist_len=16, **kw)
+    base = dict(name="graph", layers=1, batch=1, kv_heads=3, g=4, head_dim=128, kv_dtype="bf16", t0=1000, block=16,
+                hist_len=16, budget_tokens=256, n_sink=1, n_local=2, c1=8, c2=8, steps=8, calib_every=4, seed=11,
+                value_scale=1.0)
+    base.update(kw)
+    w = Workload(**base)
     run = DecodeRun(w, dev)
     run.set_weights(predictor_weights(w))
     K, V = kv_cache(w, dev)
